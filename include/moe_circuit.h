@@ -1,0 +1,161 @@
+/*
+ * moe_circuit.h -- C ABI of the MI355X (gfx950) library for one receiving GPU's MoE
+ * dispatch -> compute -> combine under a circuit schedule.
+ *
+ * Paper: "Birkhoff Decompositions and Photonic Interconnects - Wait! Don't Forget the Compute!"
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns every
+ *     buffer; the library neither allocates nor frees device memory and keeps no state between
+ *     calls except the optional kernel-timing table below.
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls validate their arguments
+ *     on the host, enqueue their kernels on that stream and return without synchronising.
+ *   - Return value: MOE_OK or a negative moe_status.  Nothing throws across this boundary.  On an
+ *     argument error nothing has been enqueued.
+ *   - Results are deterministic: the same input bytes give the same output bytes.
+ *   - Notation: N ranks, E experts (E % N == 0, expert e lives on rank e / (E/N), E_loc = E/N),
+ *     T tokens per rank, topk experts per token, r the receiving rank, kmax the cap on matchings.
+ */
+#ifndef MOE_CIRCUIT_H
+#define MOE_CIRCUIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int moe_status;
+#define MOE_OK                     0
+#define MOE_ERR_INVALID_ARG       (-1)  /* NULL where a buffer is required, negative size, ... */
+#define MOE_ERR_UNSUPPORTED_SHAPE (-2)  /* shape outside what the kernels are built for       */
+#define MOE_ERR_WORKSPACE         (-3)  /* workspace missing or too small                      */
+#define MOE_ERR_HIP               (-4)  /* a HIP runtime call failed (see moe_last_hip_error)  */
+
+#define MOE_MAX_RANKS   128     /* largest N of the decomposition kernels (residual lives in LDS) */
+#define MOE_MAX_EXPERTS 4096    /* largest E of the histogram kernel                              */
+
+/* flags of the decomposition calls */
+#define MOE_DECOMP_ZERO_DIAGONAL 1  /* treat the diagonal (tokens whose expert is local) as zero */
+
+/* weight formats of moe_expert_ffn_sliced */
+#define MOE_W_BF16            0   /* bfloat16                                                     */
+#define MOE_W_FP8_E4M3_B128   1   /* OCP FP8 E4M3 codes + one float scale per 128 x 128 block      */
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_route_histogram -- Section 2.1 (dispatch) / Section 3 (the all-to-all communication
+ * matrix between ranks).  For each of L independent layers:
+ *     expert_counts[l][s][e] = #{(t, j) : ids[l][s][t][j] == e}
+ *     traffic[l][s][q]       = sum of expert_counts[l][s][e] over the experts e of rank q
+ * i.e. every (token, expert) assignment is counted once, local ones (q == s) included.
+ *   ids            in   int32 [L][N][T][topk]; values outside [0, E) are ignored
+ *   traffic        out  int32 [L][N][N], row = source rank, column = destination rank; overwritten
+ *   expert_counts  out  int32 [L][N][E], overwritten; may be NULL
+ * Limits: 1 <= N, E % N == 0, E <= MOE_MAX_EXPERTS, L*N*T*topk < 2^31.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_route_histogram(const int32_t* ids, int L, int N, int T, int topk, int E,
+                               int32_t* traffic, int32_t* expert_counts, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_decompose_greedy -- Section 3.2 (greedy max-weight decomposition).  For each of B
+ * matrices: R <- A; while R != 0 and fewer than kmax matchings were emitted: sigma <- a
+ * maximum-weight perfect matching of R (among equally heavy ones the lexicographically
+ * smallest sequence sigma(0), sigma(1), ...); duration <- max_i R[i][sigma(i)] (a matching lasts
+ * as long as its heaviest pair, Section 3.3); R[i][sigma(i)] <- 0 for all i (each matched pair
+ * ships everything it has).
+ *   mats       in   int32 [B][N][N], entries >= 0, N * max entry < 2^31
+ *   perms      out  uint8 [B][kmax][N], perms[b][t][i] = sigma_t(i); may be NULL
+ *   durations  out  int32 [B][kmax]; may be NULL
+ *   counts     out  int32 [B]  number of matchings emitted (<= kmax)
+ *   residual   out  int32 [B][N][N]  R at exit (all zero unless the cap stopped it); may be NULL
+ *   hashes     out  uint64 [B]; may be NULL.  FNV-1a (64 bit) over the byte stream
+ *                   sigma_t(0..N-1), duration_t (4 bytes little endian), t = 0..count-1
+ * Entries of perms / durations at t >= counts[b] are left untouched.
+ * Limits: 1 <= N <= MOE_MAX_RANKS, kmax >= 0, B >= 0.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_decompose_greedy(const int32_t* mats, int B, int N, int kmax, int flags,
+                                uint8_t* perms, int32_t* durations, int32_t* counts,
+                                int32_t* residual, uint64_t* hashes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_decompose_bvn -- Section 3.1 (Birkhoff-von Neumann decomposition, the baseline).  BvN
+ * needs equal line sums; instead of the paper's Sinkhorn-Knopp scaling the matrix is balanced
+ * exactly with integer padding: Tstar = the largest row or column sum, the row and column
+ * deficits are filled by the north-west-corner rule, P = A + padding.  Then, while P != 0 and
+ * fewer than kmax matchings: sigma <- the lexicographically smallest perfect matching inside
+ * {P > 0}; lambda <- min_i P[i][sigma(i)]; P -= lambda * P_sigma.  Uncapped, sum(lambda) = Tstar
+ * and sum(lambda_t * P_sigma_t) = A + padding exactly; at most (N-1)^2 + 1 matchings.
+ *   arguments as moe_decompose_greedy; durations holds lambda_t; residual is the padded residual;
+ *   pad_total  out  int32 [B]  Tstar; may be NULL
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_decompose_bvn(const int32_t* mats, int B, int N, int kmax, int flags,
+                             uint8_t* perms, int32_t* durations, int32_t* counts,
+                             int32_t* residual, int32_t* pad_total, uint64_t* hashes,
+                             void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_slice_table -- Sections 2.2 and 4.1: per matching a receiver hears from exactly one
+ * source and its experts may start as soon as that batch has arrived.  For receiving rank r
+ * this builds the row boundaries of the token batch each matching delivers.
+ * Slices: 0 = local assignments (source r); 1 + t = delivered by matching t, t < kmax (empty for
+ * t >= *count); kmax + 1 = everything the capped schedule did not ship.  On matching t the pair
+ * (s, sigma_t(s) == r) ships min(remaining, duration_t) assignments, first-in-first-out in the
+ * order (token, slot) of source s restricted to experts on r.  Inside a slice rows are grouped
+ * by local expert.
+ *   ids        in   int32 [N][T][topk]
+ *   traffic    in   int32 [N][N]   (from moe_route_histogram, diagonal included)
+ *   perms      in   uint8 [kmax][N], durations in int32 [kmax], count in int32 [1]
+ *   offsets    out  int32 [(kmax+2)*E_loc + 1], group g = slice*E_loc + local expert,
+ *                   offsets[0] = 0, offsets[last] = rows received by r
+ *   workspace       moe_slice_table_workspace_bytes(N, kmax, E) bytes
+ * ------------------------------------------------------------------------------------------- */
+size_t     moe_slice_table_workspace_bytes(int N, int kmax, int E);
+moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk, int E, int r,
+                           const int32_t* traffic, const uint8_t* perms, const int32_t* durations,
+                           const int32_t* count, int kmax, int32_t* offsets,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_expert_ffn_sliced -- Section 2.1 (compute: each expert processes its assigned tokens),
+ * issued for all slices of a schedule at once so that no launch is paid per matching
+ * (Section 2.2: fixed launch / synchronisation overheads dominate small batches).
+ * For every group g = slice*E_loc + e and every row m in [offsets[g], offsets[g+1]):
+ *     y[m] = ( silu(x[m] Wg_e^T) * (x[m] Wu_e^T) ) Wd_e^T ,  silu(z) = z / (1 + exp(-z))
+ * with bf16 inputs, fp32 accumulation, the hidden activation rounded to bf16 once, y to bf16.
+ *   x          in   bf16 [M][d]      grouped rows (slice-major, then local expert)
+ *   offsets    in   int32 [S*E_loc + 1], non-decreasing, offsets[0] = 0, offsets[last] <= M
+ *   w_gate,w_up in  [E_loc][f][d]    out-feature major (each output's d inputs contiguous)
+ *   w_down     in   [E_loc][d][f]
+ *   s_gate,s_up in  float [E_loc][f/128][d/128], s_down float [E_loc][d/128][f/128]
+ *                   (MOE_W_FP8_E4M3_B128 only, else NULL): weight = decode(code) * scale
+ *   y          out  bf16 [M][d]; rows >= offsets[last] are left untouched
+ *   workspace       moe_ffn_workspace_bytes(M, d, f) bytes (holds the hidden activations)
+ * Limits: d % 256 == 0, f % 128 == 0, S*E_loc <= 65536, M*max(d,f) < 2^31.
+ * ------------------------------------------------------------------------------------------- */
+size_t     moe_ffn_workspace_bytes(int M, int d, int f);
+moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, int S, int E_loc,
+                                 int d, int f, int weight_format,
+                                 const void* w_gate, const void* w_up, const void* w_down,
+                                 const float* s_gate, const float* s_up, const float* s_down,
+                                 void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Kernel timing (measurement aid).  While enabled, every kernel launch of this library is
+ * bracketed by HIP events on the caller's stream.  moe_kernel_timing_read synchronises those
+ * events, adds them up per kernel name and resets the table.
+ *   names  host out  up to `cap` pointers to static strings
+ *   total_ms, launches  host out  summed duration and number of launches per name
+ * Returns the number of distinct kernel names (<= cap) or a negative moe_status.
+ * Not thread safe; intended for single-threaded benchmarks.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_kernel_timing_enable(int on);
+int        moe_kernel_timing_read(const char** names, float* total_ms, int* launches, int cap);
+
+/* Text of the last HIP error seen by this library in the calling process (host pointer). */
+const char* moe_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_CIRCUIT_H */

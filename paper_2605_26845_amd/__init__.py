@@ -1,0 +1,251 @@
+"""Python binding of libmoecircuit (MI355X / gfx950).
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the C ABI
+declared in include/moe_circuit.h.  torch is used for device memory and streams.  There is no
+CPU fallback: if the shared library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import glob
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_LIB_PATH = os.path.join(_HERE, "libmoecircuit.so")
+_INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
+
+MOE_DECOMP_ZERO_DIAGONAL = 1
+MOE_W_BF16 = 0
+MOE_W_FP8_E4M3_B128 = 1
+MOE_MAX_RANKS = 128
+
+_STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAPE", -3: "MOE_ERR_WORKSPACE",
+           -4: "MOE_ERR_HIP"}
+
+EXPORTS = [
+    "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
+    "moe_slice_table", "moe_ffn_workspace_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
+    "moe_kernel_timing_read", "moe_last_hip_error",
+]
+
+_lib = None
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every HIP source for gfx950 into libmoecircuit.so (in-tree)."""
+    srcs = sorted(glob.glob(os.path.join(_CSRC, "*.hip")))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", _INCLUDE, "-o", _LIB_PATH] + srcs
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if res.returncode != 0:
+        raise MoeError("hipcc failed:\n" + err)
+    if verbose and err.strip():
+        print(err)
+    return _LIB_PATH
+
+
+def load():
+    """Load the shared library (built beforehand by build()); fails loudly if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise MoeError("libmoecircuit.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.moe_route_histogram.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp]
+    L.moe_route_histogram.restype = ci
+    L.moe_decompose_greedy.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    L.moe_decompose_greedy.restype = ci
+    L.moe_decompose_bvn.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+    L.moe_decompose_bvn.restype = ci
+    L.moe_slice_table_workspace_bytes.argtypes = [ci, ci, ci]
+    L.moe_slice_table_workspace_bytes.restype = sz
+    L.moe_slice_table.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, sz, vp]
+    L.moe_slice_table.restype = ci
+    L.moe_ffn_workspace_bytes.argtypes = [ci, ci, ci]
+    L.moe_ffn_workspace_bytes.restype = sz
+    L.moe_expert_ffn_sliced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_expert_ffn_sliced.restype = ci
+    L.moe_kernel_timing_enable.argtypes = [ci]
+    L.moe_kernel_timing_enable.restype = ci
+    L.moe_kernel_timing_read.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
+                                         ctypes.POINTER(ctypes.c_int), ci]
+    L.moe_kernel_timing_read.restype = ci
+    L.moe_last_hip_error.argtypes = []
+    L.moe_last_hip_error.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        detail = ""
+        if rc == -4:
+            detail = ": " + (load().moe_last_hip_error() or b"").decode()
+        raise MoeError("%s -> %s%s" % (what, _STATUS.get(rc, str(rc)), detail))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_check(t, dtype, name):
+    import torch
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise MoeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dtype))
+
+
+# ---------------------------------------------------------------------------------------------
+def moe_route_histogram(ids, E: int, traffic=None, expert_counts=None, want_counts: bool = True):
+    """ids int32 [N][T][topk] or [L][N][T][topk] -> (traffic [..][N][N], expert_counts [..][N][E] or None)."""
+    import torch
+    _dev_check(ids, torch.int32, "ids")
+    batched = ids.dim() == 4
+    L = ids.shape[0] if batched else 1
+    N, T, topk = ids.shape[-3:]
+    shp = (L, N) if batched else (N,)
+    if traffic is None:
+        traffic = torch.empty(shp + (N,), dtype=torch.int32, device=ids.device)
+    if expert_counts is None and want_counts:
+        expert_counts = torch.empty(shp + (E,), dtype=torch.int32, device=ids.device)
+    _dev_check(traffic, torch.int32, "traffic")
+    _dev_check(expert_counts, torch.int32, "expert_counts")
+    _check(load().moe_route_histogram(_ptr(ids), L, N, T, topk, E, _ptr(traffic), _ptr(expert_counts), _stream()),
+           "moe_route_histogram")
+    return traffic, expert_counts
+
+
+def _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out):
+    import torch
+    B, N, _ = mats.shape
+    dev = mats.device
+    out = dict(out or {})
+    if "perms" not in out:
+        out["perms"] = torch.zeros((B, kmax, N), dtype=torch.uint8, device=dev) if want_perms else None
+    if "durations" not in out:
+        out["durations"] = torch.zeros((B, kmax), dtype=torch.int32, device=dev)
+    if "counts" not in out:
+        out["counts"] = torch.zeros((B,), dtype=torch.int32, device=dev)
+    if "residual" not in out:
+        out["residual"] = torch.empty((B, N, N), dtype=torch.int32, device=dev) if want_residual else None
+    if "hashes" not in out:
+        out["hashes"] = torch.zeros((B,), dtype=torch.int64, device=dev) if want_hashes else None
+    return out
+
+
+def moe_decompose_greedy(mats, kmax: int, zero_diag: bool = False, want_perms=True, want_residual=True,
+                         want_hashes=False, out=None):
+    """mats int32 [B][N][N] -> dict(perms, durations, counts, residual, hashes) of device tensors."""
+    import torch
+    _dev_check(mats, torch.int32, "mats")
+    B, N, _ = mats.shape
+    o = _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out)
+    _check(load().moe_decompose_greedy(_ptr(mats), B, N, kmax, MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0,
+                                       _ptr(o["perms"]), _ptr(o["durations"]), _ptr(o["counts"]), _ptr(o["residual"]),
+                                       _ptr(o["hashes"]), _stream()), "moe_decompose_greedy")
+    return o
+
+
+def moe_decompose_bvn(mats, kmax: int, zero_diag: bool = False, want_perms=True, want_residual=True,
+                      want_hashes=False, out=None):
+    """As moe_decompose_greedy, plus pad_total int32 [B]."""
+    import torch
+    _dev_check(mats, torch.int32, "mats")
+    B, N, _ = mats.shape
+    o = _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out)
+    if "pad_total" not in o:
+        o["pad_total"] = torch.zeros((B,), dtype=torch.int32, device=mats.device)
+    _check(load().moe_decompose_bvn(_ptr(mats), B, N, kmax, MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0,
+                                    _ptr(o["perms"]), _ptr(o["durations"]), _ptr(o["counts"]), _ptr(o["residual"]),
+                                    _ptr(o["pad_total"]), _ptr(o["hashes"]), _stream()), "moe_decompose_bvn")
+    return o
+
+
+def moe_slice_table(ids, E: int, r: int, traffic, perms, durations, count, kmax: int, offsets=None, workspace=None):
+    """ids [N][T][topk], traffic [N][N], perms uint8 [kmax][N], durations [kmax], count [1] -> offsets."""
+    import torch
+    _dev_check(ids, torch.int32, "ids")
+    _dev_check(traffic, torch.int32, "traffic")
+    _dev_check(perms, torch.uint8, "perms")
+    _dev_check(durations, torch.int32, "durations")
+    _dev_check(count, torch.int32, "count")
+    N, T, topk = ids.shape
+    e_loc = E // N
+    if offsets is None:
+        offsets = torch.empty(((kmax + 2) * e_loc + 1,), dtype=torch.int32, device=ids.device)
+    need = load().moe_slice_table_workspace_bytes(N, kmax, E)
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=ids.device)
+    _check(load().moe_slice_table(_ptr(ids), N, T, topk, E, r, _ptr(traffic), _ptr(perms), _ptr(durations), _ptr(count),
+                                  kmax, _ptr(offsets), _ptr(workspace), workspace.numel(), _stream()), "moe_slice_table")
+    return offsets
+
+
+def moe_ffn_workspace_bytes(M: int, d: int, f: int) -> int:
+    return int(load().moe_ffn_workspace_bytes(M, d, f))
+
+
+def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down=None,
+                          y=None, workspace=None):
+    """x bf16 [M][d]; offsets int32 [S*E_loc+1]; bf16 weights (w_gate,w_up [E_loc][f][d], w_down [E_loc][d][f]) or
+    uint8 E4M3 codes with float32 block scales -> y bf16 [M][d]."""
+    import torch
+    _dev_check(x, torch.bfloat16, "x")
+    _dev_check(offsets, torch.int32, "offsets")
+    M, d = x.shape
+    f = w_gate.shape[1]
+    fp8 = w_gate.dtype == torch.uint8
+    wdt = torch.uint8 if fp8 else torch.bfloat16
+    for name, w in (("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
+        _dev_check(w, wdt, name)
+    for name, sc in (("s_gate", s_gate), ("s_up", s_up), ("s_down", s_down)):
+        _dev_check(sc, torch.float32, name)
+    if tuple(w_gate.shape) != (E_loc, f, d) or tuple(w_up.shape) != (E_loc, f, d) or tuple(w_down.shape) != (E_loc, d, f):
+        raise MoeError("weight shapes must be w_gate/w_up [E_loc][f][d], w_down [E_loc][d][f]")
+    if offsets.numel() != S * E_loc + 1:
+        raise MoeError("offsets must have S*E_loc+1 entries")
+    if y is None:
+        y = torch.empty_like(x)
+    _dev_check(y, torch.bfloat16, "y")
+    need = moe_ffn_workspace_bytes(M, d, f)
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=x.device)
+    _check(load().moe_expert_ffn_sliced(_ptr(x), _ptr(offsets), M, S, E_loc, d, f,
+                                        MOE_W_FP8_E4M3_B128 if fp8 else MOE_W_BF16, _ptr(w_gate), _ptr(w_up),
+                                        _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(y), _ptr(workspace),
+                                        workspace.numel(), _stream()), "moe_expert_ffn_sliced")
+    return y
+
+
+def moe_kernel_timing_enable(on: bool):
+    _check(load().moe_kernel_timing_enable(1 if on else 0), "moe_kernel_timing_enable")
+
+
+def moe_kernel_timing_read(cap: int = 32):
+    """-> {kernel name: (total_ms, launches)}; synchronises the recorded events and resets the table."""
+    names = (ctypes.c_char_p * cap)()
+    ms = (ctypes.c_float * cap)()
+    n_l = (ctypes.c_int * cap)()
+    n = load().moe_kernel_timing_read(names, ms, n_l, cap)
+    if n < 0:
+        _check(n, "moe_kernel_timing_read")
+    return {names[i].decode(): (float(ms[i]), int(n_l[i])) for i in range(n)}

@@ -1,0 +1,583 @@
+// moe_decompose_greedy / moe_decompose_bvn: traffic matrix -> list of (permutation, duration).
+//
+// One 64-lane wavefront owns one matrix.  The residual (N x N int32, up to 64 KiB) lives in LDS;
+// everything else (dual variables, matchings, adjacency bit masks) lives in registers, lane c
+// holding column c (and column c+64 when N > 64) and, for row-indexed state, row c.  A single
+// wavefront needs no barriers: cross-lane traffic is DPP reductions, ballots and readlane.
+//
+//   greedy (Section 3.2): maximum-weight perfect matching by shortest augmenting paths with
+//     dual variables (the Jonker-Volgenant / Hungarian family the paper cites), duals kept warm
+//     from one matching to the next (weights only ever decrease, so they stay feasible).
+//   BvN (Section 3.1): integer padding to equal line sums, then perfect matchings inside the
+//     support, repaired incrementally after every subtraction.
+//   Both return the lexicographically smallest optimal permutation: the optimal permutations are
+//     the perfect matchings of the tight graph (greedy) or of the support (BvN); rows are fixed
+//     in order, each by one breadth-first search over alternating paths on 128-bit lane masks.
+#include "common.hpp"
+#include <limits.h>
+
+namespace {
+
+constexpr unsigned long long FNV_OFFSET = 14695981039346656037ULL;
+constexpr unsigned long long FNV_PRIME = 1099511628211ULL;
+
+// ------------------------------------------------------------------------------ wave primitives
+__device__ __forceinline__ int rdlane(int v, int l) {
+    return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+// All 64 lanes must be active.
+__device__ __forceinline__ int wave_min(int x) {
+    x = min(x, dpp<0xB1>(x));    // quad_perm [1,0,3,2]
+    x = min(x, dpp<0x4E>(x));    // quad_perm [2,3,0,1]
+    x = min(x, dpp<0x141>(x));   // row_half_mirror
+    x = min(x, dpp<0x140>(x));   // row_mirror: every lane of a 16-lane row now holds the row's min
+    int a = __builtin_amdgcn_readlane(x, 0), b = __builtin_amdgcn_readlane(x, 16);
+    int c = __builtin_amdgcn_readlane(x, 32), d = __builtin_amdgcn_readlane(x, 48);
+    return min(min(a, b), min(c, d));
+}
+__device__ __forceinline__ int wave_max(int x) { return -wave_min(-x); }      // callers pass x > INT_MIN
+__device__ __forceinline__ int wave_sum(int x) {
+    x += dpp<0xB1>(x);
+    x += dpp<0x4E>(x);
+    x += dpp<0x141>(x);
+    x += dpp<0x140>(x);
+    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
+           __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
+}
+__device__ __forceinline__ unsigned long long ballot64(bool p) { return __ballot(p); }
+
+// lane-distributed arrays: element idx lives in lane idx & 63, slot idx >> 6
+template <int NPL>
+__device__ __forceinline__ int bcast(const int (&a)[NPL], int idx) {
+    int r = rdlane(a[0], idx & 63);
+    if (NPL > 1) { int r1 = rdlane(a[NPL - 1], idx & 63); r = (idx >> 6) ? r1 : r; }
+    return r;
+}
+template <int NPL>
+__device__ __forceinline__ void set_at(int (&a)[NPL], int idx, int val, int lane) {
+#pragma unroll
+    for (int s = 0; s < NPL; ++s)
+        if (lane == (idx & 63) && s == (idx >> 6)) a[s] = val;
+}
+
+// N-bit column/row sets as NPL 64-bit words
+template <int NPL> struct Mask {
+    unsigned long long w[NPL];
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) w[k] = 0;
+    }
+    __device__ __forceinline__ bool any() const {
+        unsigned long long o = 0;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) o |= w[k];
+        return o != 0;
+    }
+    __device__ __forceinline__ bool test(int i) const {
+        unsigned long long x = w[0];
+        if (NPL > 1) x = (i >> 6) ? w[NPL - 1] : x;
+        return (x >> (i & 63)) & 1ULL;
+    }
+    __device__ __forceinline__ void set(int i) {
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) if (k == (i >> 6)) w[k] |= 1ULL << (i & 63);
+    }
+    __device__ __forceinline__ void reset(int i) {
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) if (k == (i >> 6)) w[k] &= ~(1ULL << (i & 63));
+    }
+    __device__ __forceinline__ int first() const {        // index of the lowest set bit (any() must hold)
+        int r = -1;
+#pragma unroll
+        for (int k = NPL - 1; k >= 0; --k) if (w[k]) r = 64 * k + __builtin_ctzll(w[k]);
+        return r;
+    }
+};
+template <int NPL>
+__device__ __forceinline__ Mask<NPL> operator&(const Mask<NPL>& a, const Mask<NPL>& b) {
+    Mask<NPL> r;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) r.w[k] = a.w[k] & b.w[k];
+    return r;
+}
+// bits strictly below position i
+template <int NPL>
+__device__ __forceinline__ Mask<NPL> below(int i) {
+    Mask<NPL> r;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+        int rel = i - 64 * k;
+        r.w[k] = rel <= 0 ? 0ULL : (rel >= 64 ? ~0ULL : ((1ULL << rel) - 1ULL));
+    }
+    return r;
+}
+// uniform copy of the mask held by row-lane `row`
+template <int NPL>
+__device__ __forceinline__ Mask<NPL> bcast_mask(const Mask<NPL> (&m)[NPL], int row) {
+    Mask<NPL> r;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+        int lo[NPL], hi[NPL];
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) { lo[s] = (int)(m[s].w[k] & 0xFFFFFFFFULL); hi[s] = (int)(m[s].w[k] >> 32); }
+        unsigned int l = (unsigned int)bcast<NPL>(lo, row), h = (unsigned int)bcast<NPL>(hi, row);
+        r.w[k] = ((unsigned long long)h << 32) | l;
+    }
+    return r;
+}
+
+// ------------------------------------------------------------------------------ shared pieces
+// Copy one matrix into LDS (optionally with the diagonal forced to zero).
+__device__ __forceinline__ void load_matrix(const int32_t* __restrict__ A, int32_t* R, int N, bool zero_diag, int lane) {
+    const int total = N * N;
+    if ((total & 3) == 0 && (((uintptr_t)A) & 15) == 0) {
+        const int4* src = reinterpret_cast<const int4*>(A);
+        int4* dst = reinterpret_cast<int4*>(R);
+        for (int x = lane; x < total / 4; x += MOE_WAVE) dst[x] = src[x];
+    } else {
+        for (int x = lane; x < total; x += MOE_WAVE) R[x] = A[x];
+    }
+    __syncthreads();
+    if (zero_diag) {
+        for (int i = lane; i < N; i += MOE_WAVE) R[i * N + i] = 0;
+        __syncthreads();
+    }
+}
+__device__ __forceinline__ void store_matrix(const int32_t* R, int32_t* __restrict__ out, int N, int lane) {
+    const int total = N * N;
+    for (int x = lane; x < total; x += MOE_WAVE) out[x] = R[x];
+}
+
+// Adjacency masks: row-lane r gets {j : pred(R[r][j], r, j)}; built row by row with ballots so
+// that LDS reads are conflict free.
+template <int NPL, typename Pred>
+__device__ __forceinline__ void build_masks(const int32_t* R, int N, int lane, Mask<NPL> (&tm)[NPL], Pred pred) {
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) tm[s].clear();
+    for (int i = 0; i < N; ++i) {
+        Mask<NPL> row;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int j = lane + 64 * s;
+            bool on = (j < N) && pred(R[i * N + (j < N ? j : 0)], i, s);
+            row.w[s] = ballot64(on);
+        }
+#pragma unroll
+        for (int s = 0; s < NPL; ++s)
+            if (lane == (i & 63) && s == (i >> 6)) tm[s] = row;
+    }
+}
+
+// One level of the alternating breadth-first search used by both the lexicographic pass and
+// the BvN repair.  Rows satisfying `eligible` that touch a reached column become visited and
+// remember that column; returns the set of rows visited in this level.
+template <int NPL>
+__device__ __forceinline__ Mask<NPL> bfs_visit_rows(const Mask<NPL> (&tm)[NPL], const Mask<NPL>& reached, int N, int lane,
+                                                    int min_row_exclusive, bool (&visited)[NPL], int (&parent)[NPL]) {
+    Mask<NPL> vm;
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) {
+        int row = lane + 64 * s;
+        Mask<NPL> hit = tm[s] & reached;
+        bool nv = row > min_row_exclusive && row < N && !visited[s] && hit.any();
+        if (nv) { visited[s] = true; parent[s] = hit.first(); }
+        vm.w[s] = ballot64(nv);
+    }
+    return vm;
+}
+// Columns whose current owner row is in `rows` join `reached`.
+template <int NPL>
+__device__ __forceinline__ void bfs_reach_cols(const int (&p)[NPL], const Mask<NPL>& rows, int N, int lane, Mask<NPL>& reached) {
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) {
+        int c = lane + 64 * s;
+        bool nr = c < N && p[s] >= 0 && rows.test(p[s]);
+        reached.w[s] |= ballot64(nr);
+    }
+}
+// Re-route along the parents: `row` takes `col`, the previous owner of `col` takes its parent
+// column, ... until the free column `stop_col` has been taken.
+template <int NPL>
+__device__ __forceinline__ void apply_path(int row, int col, int stop_col, int (&sigma)[NPL], int (&p)[NPL],
+                                           const int (&parent)[NPL], int lane, int N) {
+    for (int guard = 0; guard <= N; ++guard) {
+        int prev_owner = bcast<NPL>(p, col);
+        set_at<NPL>(sigma, row, col, lane);
+        set_at<NPL>(p, col, row, lane);
+        if (col == stop_col) break;
+        row = prev_owner;
+        col = bcast<NPL>(parent, prev_owner);
+    }
+}
+
+// Turn the perfect matching (sigma: row -> col, p: col -> row) of the graph `tm` into the
+// lexicographically smallest perfect matching of that graph.
+template <int NPL>
+__device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, int lane, int (&sigma)[NPL], int (&p)[NPL]) {
+    Mask<NPL> fixed_cols;
+    fixed_cols.clear();
+    for (int i = 0; i < N; ++i) {
+        int cur = bcast<NPL>(sigma, i);
+        Mask<NPL> cand = bcast_mask<NPL>(tm, i) & below<NPL>(cur);
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) cand.w[k] &= ~fixed_cols.w[k];
+        if (cand.any()) {
+            // which columns can be vacated by re-routing rows > i, the column `cur` being free?
+            Mask<NPL> reached;
+            reached.clear();
+            reached.set(cur);
+            bool visited[NPL];
+            int parent[NPL];
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+            const int best = cand.first();
+            for (int level = 0; level < N; ++level) {
+                Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, i, visited, parent);
+                if (!vm.any()) break;
+                bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                if (reached.test(best)) break;
+            }
+            Mask<NPL> hit = cand & reached;
+            if (hit.any()) {
+                int j = hit.first();
+                apply_path<NPL>(i, j, cur, sigma, p, parent, lane, N);
+                cur = j;
+            }
+        }
+        fixed_cols.set(cur);
+    }
+}
+
+struct Fnv {
+    unsigned long long h;
+    __device__ __forceinline__ void byte(unsigned int b) { h = (h ^ (unsigned long long)(b & 0xFF)) * FNV_PRIME; }
+};
+
+template <int NPL>
+__device__ __forceinline__ void emit_matching(const int (&sigma)[NPL], int duration, int N, int lane, int t,
+                                              uint8_t* perms_b, int32_t* dur_b, Fnv* fnv) {
+    if (perms_b) {
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int i = lane + 64 * s;
+            if (i < N) perms_b[(size_t)t * N + i] = (uint8_t)sigma[s];
+        }
+    }
+    if (dur_b && lane == 0) dur_b[t] = duration;
+    if (fnv) {
+        for (int i = 0; i < N; ++i) fnv->byte((unsigned int)bcast<NPL>(sigma, i));
+        unsigned int d = (unsigned int)duration;
+        for (int k = 0; k < 4; ++k) fnv->byte(d >> (8 * k));
+    }
+}
+
+// ------------------------------------------------------------------------------ greedy kernel
+template <int NPL>
+__global__ __launch_bounds__(MOE_WAVE)
+void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
+                   int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
+                   unsigned long long* __restrict__ hashes) {
+    extern __shared__ int32_t R[];
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x;
+    load_matrix(mats + (size_t)b * N * N, R, N, flags & MOE_DECOMP_ZERO_DIAGONAL, lane);
+
+    // feasible start: u_i = row maximum, v_j = 0  (u_i + v_j >= R_ij)
+    int u[NPL], v[NPL], p[NPL], sigma[NPL];
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) { u[s] = 0; v[s] = 0; p[s] = -1; sigma[s] = -1; }
+    int nnz = 0;
+    for (int i = 0; i < N; ++i) {
+        int m = 0, pos = 0;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int j = lane + 64 * s;
+            int x = j < N ? R[i * N + j] : 0;
+            m = max(m, x);
+            pos += __popcll(ballot64(x > 0));
+        }
+        m = wave_max(m);
+        nnz += pos;
+        set_at<NPL>(u, i, m, lane);
+    }
+
+    Fnv fnv{FNV_OFFSET};
+    uint8_t* perms_b = perms ? perms + (size_t)b * kmax * N : nullptr;
+    int32_t* dur_b = durations ? durations + (size_t)b * kmax : nullptr;
+    int t = 0;
+    while (t < kmax && nnz > 0) {
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
+        // ---- maximum-weight perfect matching: one shortest augmenting path per row
+        for (int r = 0; r < N; ++r) {
+            int minv[NPL], way[NPL];
+            bool used[NPL], intree[NPL];
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) { minv[s] = INT_MAX; way[s] = -1; used[s] = false; intree[s] = false; }
+            int i0 = r, j0 = -1;
+            for (int step = 0; step < N; ++step) {
+#pragma unroll
+                for (int s = 0; s < NPL; ++s)
+                    if (lane == (i0 & 63) && s == (i0 >> 6)) intree[s] = true;
+                const int ui0 = bcast<NPL>(u, i0);
+                const int32_t* row = R + i0 * N;
+                int local = INT_MAX;
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) {
+                    int j = lane + 64 * s;
+                    if (j < N && !used[s]) {
+                        int slack = ui0 + v[s] - row[j];
+                        if (slack < minv[s]) { minv[s] = slack; way[s] = j0; }
+                        local = min(local, minv[s]);
+                    }
+                }
+                const int delta = wave_min(local);
+                int j1 = -1;
+#pragma unroll
+                for (int s = NPL - 1; s >= 0; --s) {
+                    int j = lane + 64 * s;
+                    unsigned long long m = ballot64(j < N && !used[s] && minv[s] == delta);
+                    if (m) j1 = 64 * s + __builtin_ctzll(m);
+                }
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) {
+                    if (used[s]) v[s] += delta;
+                    else if (minv[s] != INT_MAX) minv[s] -= delta;
+                    if (intree[s]) u[s] -= delta;
+                }
+#pragma unroll
+                for (int s = 0; s < NPL; ++s)
+                    if (lane == (j1 & 63) && s == (j1 >> 6)) used[s] = true;
+                j0 = j1;
+                i0 = bcast<NPL>(p, j1);
+                if (i0 < 0) break;
+            }
+            // flip the path back to row r
+            for (int guard = 0; guard <= N; ++guard) {
+                int j1 = bcast<NPL>(way, j0);
+                int i = r;
+                if (j1 >= 0) i = bcast<NPL>(p, j1);
+                set_at<NPL>(p, j0, i, lane);
+                set_at<NPL>(sigma, i, j0, lane);
+                if (j1 < 0) break;
+                j0 = j1;
+            }
+        }
+        // ---- canonical optimum: lexicographically smallest perfect matching of the tight graph
+        Mask<NPL> tm[NPL];
+        {
+            int vv[NPL];
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) vv[s] = v[s];
+            build_masks<NPL>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
+        }
+        lex_smallest<NPL>(tm, N, lane, sigma, p);
+        // ---- ship whole entries; the matching lasts as long as its heaviest pair
+        int dmax = 0, pos = 0;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int i = lane + 64 * s;
+            int x = 0;
+            if (i < N) { x = R[i * N + sigma[s]]; R[i * N + sigma[s]] = 0; }
+            dmax = max(dmax, x);
+            pos += __popcll(ballot64(x > 0));
+        }
+        dmax = wave_max(dmax);
+        nnz -= pos;
+        __syncthreads();
+        emit_matching<NPL>(sigma, dmax, N, lane, t, perms_b, dur_b, hashes ? &fnv : nullptr);
+        ++t;
+    }
+    if (lane == 0) {
+        counts[b] = t;
+        if (hashes) hashes[b] = fnv.h;
+    }
+    if (residual) store_matrix(R, residual + (size_t)b * N * N, N, lane);
+}
+
+// ------------------------------------------------------------------------------ BvN kernel
+template <int NPL>
+__global__ __launch_bounds__(MOE_WAVE)
+void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
+                int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
+                int32_t* __restrict__ pad_total, unsigned long long* __restrict__ hashes) {
+    extern __shared__ int32_t R[];
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x;
+    load_matrix(mats + (size_t)b * N * N, R, N, flags & MOE_DECOMP_ZERO_DIAGONAL, lane);
+
+    // ---- integer padding to equal line sums (north-west-corner fill of the deficits)
+    int rdef[NPL], cdef[NPL];
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) { rdef[s] = 0; cdef[s] = 0; }
+    for (int i = 0; i < N; ++i) {
+        int part = 0;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int j = lane + 64 * s;
+            int x = j < N ? R[i * N + j] : 0;
+            cdef[s] += x;                       // column sums accumulate in the column's lane
+            part += x;
+        }
+        set_at<NPL>(rdef, i, wave_sum(part), lane);
+    }
+    int line_max = 0;
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) line_max = max(line_max, max(rdef[s], cdef[s]));
+    const int target = wave_max(line_max);
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) {
+        int idx = lane + 64 * s;
+        rdef[s] = idx < N ? target - rdef[s] : 0;
+        cdef[s] = idx < N ? target - cdef[s] : 0;
+    }
+    {
+        int i = 0, j = 0;
+        int ri = bcast<NPL>(rdef, 0), cj = bcast<NPL>(cdef, 0);
+        for (int guard = 0; guard < 2 * N + 2 && i < N && j < N; ++guard) {
+            if (ri == 0) { ++i; if (i < N) ri = bcast<NPL>(rdef, i); continue; }
+            if (cj == 0) { ++j; if (j < N) cj = bcast<NPL>(cdef, j); continue; }
+            int dl = min(ri, cj);
+            if (lane == 0) R[i * N + j] += dl;
+            ri -= dl; cj -= dl;
+        }
+        __syncthreads();
+    }
+
+    // ---- support masks and number of positive entries
+    Mask<NPL> tm[NPL];
+    build_masks<NPL>(R, N, lane, tm, [](int x, int, int) { return x > 0; });
+    int nnz = 0;
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) {
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) c += __popcll(tm[s].w[k]);
+        nnz += wave_sum(c);
+    }
+
+    int p[NPL], sigma[NPL];
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
+    Fnv fnv{FNV_OFFSET};
+    uint8_t* perms_b = perms ? perms + (size_t)b * kmax * N : nullptr;
+    int32_t* dur_b = durations ? durations + (size_t)b * kmax : nullptr;
+    int t = 0;
+    bool broken = false;
+    while (t < kmax && nnz > 0 && !broken) {
+        // ---- repair: every free column looks for an unmatched row along an alternating path
+        Mask<NPL> free_cols;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+        while (free_cols.any() && !broken) {
+            const int cf = free_cols.first();
+            free_cols.reset(cf);
+            Mask<NPL> reached;
+            reached.clear();
+            reached.set(cf);
+            bool visited[NPL];
+            int parent[NPL];
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+            int target_row = -1;
+            for (int level = 0; level <= N; ++level) {
+                Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, -1, visited, parent);
+                if (!vm.any()) break;
+                Mask<NPL> um;                    // newly visited rows that are unmatched
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) um.w[s] = vm.w[s] & ballot64(sigma[s] < 0);
+                if (um.any()) { target_row = um.first(); break; }
+                bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+            }
+            if (target_row < 0) { broken = true; break; }     // impossible for equal line sums
+            apply_path<NPL>(target_row, bcast<NPL>(parent, target_row), cf, sigma, p, parent, lane, N);
+        }
+        if (broken) break;
+        lex_smallest<NPL>(tm, N, lane, sigma, p);
+        // ---- coefficient = smallest entry on the matching; subtract it
+        int x[NPL], lmin = INT_MAX;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int i = lane + 64 * s;
+            x[s] = i < N ? R[i * N + sigma[s]] : INT_MAX;
+            lmin = min(lmin, x[s]);
+        }
+        const int lambda = wave_min(lmin);
+        emit_matching<NPL>(sigma, lambda, N, lane, t, perms_b, dur_b, hashes ? &fnv : nullptr);
+        ++t;
+        Mask<NPL> dead_rows;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            int i = lane + 64 * s;
+            bool dead = false;
+            if (i < N) {
+                int nx = x[s] - lambda;
+                R[i * N + sigma[s]] = nx;
+                dead = nx == 0;
+            }
+            if (dead) { tm[s].reset(sigma[s]); sigma[s] = -1; }
+            dead_rows.w[s] = ballot64(dead);
+        }
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            nnz -= __popcll(dead_rows.w[s]);
+            if (p[s] >= 0 && dead_rows.test(p[s])) p[s] = -1;
+        }
+        __syncthreads();
+    }
+    if (lane == 0) {
+        counts[b] = broken ? -1 : t;
+        if (pad_total) pad_total[b] = target;
+        if (hashes) hashes[b] = fnv.h;
+    }
+    if (residual) store_matrix(R, residual + (size_t)b * N * N, N, lane);
+}
+
+moe_status check_args(const int32_t* mats, int B, int N, int kmax, int32_t* counts) {
+    if (B < 0 || N < 1 || kmax < 0 || !counts) return MOE_ERR_INVALID_ARG;
+    if (B > 0 && !mats) return MOE_ERR_INVALID_ARG;
+    if (N > MOE_MAX_RANKS) return MOE_ERR_UNSUPPORTED_SHAPE;
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" moe_status moe_decompose_greedy(const int32_t* mats, int B, int N, int kmax, int flags, uint8_t* perms,
+                                           int32_t* durations, int32_t* counts, int32_t* residual, uint64_t* hashes,
+                                           void* hip_stream) {
+    moe_status st = check_args(mats, B, N, kmax, counts);
+    if (st != MOE_OK) return st;
+    if (B == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t lds = (size_t)N * N * sizeof(int32_t);
+    moe::LaunchScope k("greedy_kernel", s);
+    if (N <= 64)
+        hipLaunchKernelGGL(greedy_kernel<1>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations,
+                           counts, residual, (unsigned long long*)hashes);
+    else
+        hipLaunchKernelGGL(greedy_kernel<2>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations,
+                           counts, residual, (unsigned long long*)hashes);
+    return k.done();
+}
+
+extern "C" moe_status moe_decompose_bvn(const int32_t* mats, int B, int N, int kmax, int flags, uint8_t* perms,
+                                        int32_t* durations, int32_t* counts, int32_t* residual, int32_t* pad_total,
+                                        uint64_t* hashes, void* hip_stream) {
+    moe_status st = check_args(mats, B, N, kmax, counts);
+    if (st != MOE_OK) return st;
+    if (B == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t lds = (size_t)N * N * sizeof(int32_t);
+    moe::LaunchScope k("bvn_kernel", s);
+    if (N <= 64)
+        hipLaunchKernelGGL(bvn_kernel<1>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts,
+                           residual, pad_total, (unsigned long long*)hashes);
+    else
+        hipLaunchKernelGGL(bvn_kernel<2>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts,
+                           residual, pad_total, (unsigned long long*)hashes);
+    return k.done();
+}

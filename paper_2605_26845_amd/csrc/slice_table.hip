@@ -1,0 +1,205 @@
+// moe_slice_table: which rows reach the receiving rank in which matching (Sections 2.2 / 4.1:
+// one source per receiver per matching; experts start when a matching's batch has arrived).
+// One workgroup per source rank: it lists the matchings in which that source is wired to the
+// receiver together with the cumulative amount shipped, then walks the source's assignments in
+// arrival order and drops each one destined to the receiver into its window.
+#include "common.hpp"
+
+namespace {
+
+constexpr int ST_THREADS = 1024;
+constexpr int ST_WAVES = ST_THREADS / MOE_WAVE;
+constexpr int WIN_CAP = 2048;      // windows of one source kept in LDS (more spill to the workspace)
+constexpr int CNT_CAP = 8192;      // (window, expert) counters of one source kept in LDS
+
+struct ScanSmem {
+    int wave_cnt[ST_WAVES];
+    unsigned long long wave_sum[ST_WAVES];
+};
+
+// Block-wide scan in thread order: exclusive count of `flag`, inclusive sum of `val`;
+// `total_*` are the block totals.  Two barriers.
+__device__ __forceinline__ void block_scan(ScanSmem& sm, bool flag, unsigned long long val, int tid, int& excl_cnt,
+                                           unsigned long long& incl_sum, int& total_cnt, unsigned long long& total_sum) {
+    const int lane = tid & 63, wave = tid >> 6;
+    unsigned long long b = __ballot(flag);
+    int wcnt_excl = __popcll(b & ((1ULL << lane) - 1ULL));
+    unsigned long long run = val;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        unsigned long long o = __shfl_up(run, off);
+        if (lane >= off) run += o;
+    }
+    if (lane == 63) { sm.wave_cnt[wave] = __popcll(b); sm.wave_sum[wave] = run; }
+    __syncthreads();
+    int cbase = 0, ctot = 0;
+    unsigned long long sbase = 0, stot = 0;
+#pragma unroll
+    for (int w = 0; w < ST_WAVES; ++w) {
+        int c = sm.wave_cnt[w];
+        unsigned long long s = sm.wave_sum[w];
+        if (w < wave) { cbase += c; sbase += s; }
+        ctot += c; stot += s;
+    }
+    __syncthreads();
+    excl_cnt = cbase + wcnt_excl;
+    incl_sum = sbase + run;
+    total_cnt = ctot;
+    total_sum = stot;
+}
+
+__global__ void st_zero_kernel(int32_t* __restrict__ sizes, int G) {
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < G; x += gridDim.x * blockDim.x) sizes[x] = 0;
+}
+
+__global__ __launch_bounds__(ST_THREADS)
+void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E, int e_loc, int r,
+                     const int32_t* __restrict__ traffic, const uint8_t* __restrict__ perms,
+                     const int32_t* __restrict__ durations, const int32_t* __restrict__ count_ptr, int kmax,
+                     int32_t* __restrict__ sizes, int2* __restrict__ win_ws) {
+    __shared__ ScanSmem sm;
+    __shared__ int2 lds_win[WIN_CAP];
+    __shared__ int lds_cnt[CNT_CAP];
+    const int tid = threadIdx.x;
+    const int s = blockIdx.x;
+    int K = *count_ptr;
+    K = K < 0 ? 0 : (K > kmax ? kmax : K);
+    const long long amount = traffic[(size_t)s * N + r];
+    int2* my_ws = win_ws + (size_t)s * kmax;
+
+    // ---- windows of this source: (slice id, cumulative amount shipped up to and including it)
+    int W = 0;
+    if (s != r) {
+        unsigned long long shipped = 0;
+        for (int t0 = 0; t0 < K; t0 += ST_THREADS) {
+            int t = t0 + tid;
+            bool flag = t < K && perms[(size_t)t * N + s] == r;
+            unsigned long long d = flag ? (unsigned long long)(unsigned int)max(durations[t], 0) : 0ULL;
+            int excl, tot;
+            unsigned long long incl, stot;
+            block_scan(sm, flag, d, tid, excl, incl, tot, stot);
+            if (flag) {
+                unsigned long long cum = shipped + incl;
+                if (cum > (unsigned long long)amount) cum = (unsigned long long)amount;
+                int2 w2 = make_int2(1 + t, (int)cum);
+                int idx = W + excl;
+                my_ws[idx] = w2;
+                if (idx < WIN_CAP) lds_win[idx] = w2;
+            }
+            W += tot;
+            shipped += stot;
+        }
+    }
+    const bool cnt_in_lds = (W + 1) * e_loc <= CNT_CAP;
+    if (cnt_in_lds)
+        for (int x = tid; x < (W + 1) * e_loc; x += ST_THREADS) lds_cnt[x] = 0;
+    __threadfence_block();
+    __syncthreads();
+    const bool win_in_lds = W <= WIN_CAP;
+
+    // ---- walk the assignments in arrival order
+    int q_base = 0;
+    const int32_t* src = ids + (size_t)s * per_src;
+    for (int x0 = 0; x0 < per_src; x0 += ST_THREADS) {
+        int x = x0 + tid;
+        int e = x < per_src ? src[x] : -1;
+        bool mine = (unsigned)e < (unsigned)E && e / e_loc == r;
+        int excl, tot;
+        unsigned long long dummy_i, dummy_t;
+        block_scan(sm, mine, 0ULL, tid, excl, dummy_i, tot, dummy_t);
+        if (mine) {
+            const int q = q_base + excl;
+            // smallest window whose cumulative amount exceeds q; W means "not shipped"
+            int lo = 0, hi = W;
+            while (lo < hi) {
+                int mid = (lo + hi) >> 1;
+                int cum = win_in_lds ? lds_win[mid].y : my_ws[mid].y;
+                if (cum > q) hi = mid; else lo = mid + 1;
+            }
+            const int el = e % e_loc;
+            if (cnt_in_lds) {
+                atomicAdd(&lds_cnt[lo * e_loc + el], 1);
+            } else {
+                int slice = s == r ? 0 : (lo < W ? (win_in_lds ? lds_win[lo].x : my_ws[lo].x) : kmax + 1);
+                atomicAdd(&sizes[(size_t)slice * e_loc + el], 1);
+            }
+        }
+        q_base += tot;
+    }
+    if (cnt_in_lds) {
+        __syncthreads();
+        for (int x = tid; x < (W + 1) * e_loc; x += ST_THREADS) {
+            int c = lds_cnt[x];
+            if (c == 0) continue;
+            int w = x / e_loc, el = x - w * e_loc;
+            int slice = s == r ? 0 : (w < W ? (win_in_lds ? lds_win[w].x : my_ws[w].x) : kmax + 1);
+            atomicAdd(&sizes[(size_t)slice * e_loc + el], c);
+        }
+    }
+}
+
+// offsets[0] = 0, offsets[g+1] = sizes[0] + ... + sizes[g]; one workgroup.
+__global__ __launch_bounds__(ST_THREADS)
+void st_scan_kernel(const int32_t* __restrict__ sizes, int G, int32_t* __restrict__ offsets) {
+    __shared__ ScanSmem sm;
+    const int tid = threadIdx.x;
+    unsigned long long base = 0;
+    if (tid == 0) offsets[0] = 0;
+    for (int g0 = 0; g0 < G; g0 += ST_THREADS) {
+        int g = g0 + tid;
+        unsigned long long v = g < G ? (unsigned long long)sizes[g] : 0ULL;
+        int excl, tot;
+        unsigned long long incl, stot;
+        block_scan(sm, false, v, tid, excl, incl, tot, stot);
+        if (g < G) offsets[g + 1] = (int32_t)(base + incl);
+        base += stot;
+    }
+}
+
+size_t sizes_bytes(int kmax, int e_loc) {
+    size_t b = ((size_t)(kmax + 2) * e_loc) * sizeof(int32_t);
+    return (b + 255) & ~(size_t)255;
+}
+
+}  // namespace
+
+extern "C" size_t moe_slice_table_workspace_bytes(int N, int kmax, int E) {
+    if (N < 1 || kmax < 0 || E < 1 || E % N != 0) return 0;
+    return sizes_bytes(kmax, E / N) + (size_t)N * (kmax > 0 ? kmax : 1) * sizeof(int2);
+}
+
+extern "C" moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk, int E, int r, const int32_t* traffic,
+                                      const uint8_t* perms, const int32_t* durations, const int32_t* count, int kmax,
+                                      int32_t* offsets, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (N < 1 || T < 0 || topk < 1 || E < 1 || kmax < 0 || r < 0 || r >= N) return MOE_ERR_INVALID_ARG;
+    if (!traffic || !count || !offsets || (kmax > 0 && (!perms || !durations))) return MOE_ERR_INVALID_ARG;
+    if (E % N != 0 || N > 256) return MOE_ERR_UNSUPPORTED_SHAPE;
+    const long long per_src = (long long)T * topk;
+    if (per_src * N >= (1LL << 31)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (per_src > 0 && !ids) return MOE_ERR_INVALID_ARG;
+    const int e_loc = E / N;
+    const long long G = (long long)(kmax + 2) * e_loc;
+    if (G >= (1LL << 30)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (!workspace || workspace_bytes < moe_slice_table_workspace_bytes(N, kmax, E)) return MOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    int32_t* sizes = (int32_t*)workspace;
+    int2* win_ws = (int2*)((char*)workspace + sizes_bytes(kmax, e_loc));
+    {
+        moe::LaunchScope k("st_zero_kernel", s);
+        int blocks = (int)((G + 255) / 256);
+        if (blocks > 256) blocks = 256;
+        hipLaunchKernelGGL(st_zero_kernel, dim3(blocks), dim3(256), 0, s, sizes, (int)G);
+        moe_status st = k.done();
+        if (st != MOE_OK) return st;
+    }
+    {
+        moe::LaunchScope k("st_count_kernel", s);
+        hipLaunchKernelGGL(st_count_kernel, dim3(N), dim3(ST_THREADS), 0, s, ids, N, (int)per_src, E, e_loc, r, traffic,
+                           perms, durations, count, kmax, sizes, win_ws);
+        moe_status st = k.done();
+        if (st != MOE_OK) return st;
+    }
+    moe::LaunchScope k("st_scan_kernel", s);
+    hipLaunchKernelGGL(st_scan_kernel, dim3(1), dim3(ST_THREADS), 0, s, sizes, (int)G, offsets);
+    return k.done();
+}

@@ -1,0 +1,347 @@
+"""GPU parity tests: every call goes through the C ABI (ctypes binding) and is compared with the
+CPU oracle on the same seeded inputs -- bit-exact for histogram, decompositions and slice table,
+max relative error <= 2e-2 (bf16 weights) / 6e-2 (fp8 weights) for the FFN."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+FFN_TOL = {"bf16": 2e-2, "fp8": 6e-2}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def dev_bf16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def host_bf16_bits(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------------------ histogram
+@pytest.mark.parametrize("name", ["tiny", "c2", "c3"])
+def test_histogram_configs(lib, name):
+    cfg = workloads.CONFIGS[name]
+    say("histogram", name)
+    ids = workloads.config_routing(cfg)
+    traffic, counts = lib.moe_route_histogram(dev(ids), cfg.E)
+    torch.cuda.synchronize()
+    rt, rc = oracle.route_histogram(ids, cfg.E)
+    assert np.array_equal(traffic.cpu().numpy(), rt)
+    assert np.array_equal(counts.cpu().numpy(), rc)
+
+
+@pytest.mark.parametrize("N,T,topk,E,L", [(3, 7, 3, 6, 1), (4, 1, 1, 4, 2), (8, 5000, 5, 64, 3), (2, 40001, 1, 4096, 1),
+                                          (16, 0, 2, 16, 1), (5, 33, 2, 640, 4)])
+def test_histogram_shapes_and_invalid_ids(lib, N, T, topk, E, L):
+    say("histogram shapes", N, T, topk, E, L)
+    rng = np.random.default_rng(N * 1000 + T)
+    ids = rng.integers(-2, E + 2, size=(L, N, T, topk), dtype=np.int64).astype(np.int32)   # includes invalid ids
+    traffic, counts = lib.moe_route_histogram(dev(ids), E)
+    t_only, none = lib.moe_route_histogram(dev(ids), E, want_counts=False)
+    torch.cuda.synchronize()
+    assert none is None
+    for l in range(L):
+        rt, rc = oracle.route_histogram(ids[l], E)
+        assert np.array_equal(traffic[l].cpu().numpy(), rt)
+        assert np.array_equal(counts[l].cpu().numpy(), rc)
+        assert np.array_equal(t_only[l].cpu().numpy(), rt)
+
+
+def test_histogram_argument_errors(lib):
+    ids = torch.zeros((2, 4, 1), dtype=torch.int32, device=DEV)
+    with pytest.raises(lib.MoeError):
+        lib.moe_route_histogram(ids, 3)                     # E % N != 0
+    with pytest.raises(lib.MoeError):
+        lib.moe_route_histogram(ids, 8192)                  # E too large
+
+
+# ------------------------------------------------------------------------------ decompositions
+def check_decomposition(lib, which, mats, kmax, zero_diag):
+    B, N, _ = mats.shape
+    fn = lib.moe_decompose_greedy if which == "greedy" else lib.moe_decompose_bvn
+    sentinel_p, sentinel_d = 0xEE, -777
+    out0 = {"perms": torch.full((B, kmax, N), sentinel_p, dtype=torch.uint8, device=DEV),
+            "durations": torch.full((B, kmax), sentinel_d, dtype=torch.int32, device=DEV)}
+    out = fn(dev(mats), kmax, zero_diag=zero_diag, want_hashes=True, out=out0)
+    torch.cuda.synchronize()
+    ref = oracle.decompose_batch(which, mats, kmax, zero_diag=zero_diag, nthreads=8)
+    counts = out["counts"].cpu().numpy()
+    assert np.array_equal(counts, ref["counts"]), (which, N, counts, ref["counts"])
+    perms = out["perms"].cpu().numpy()
+    dur = out["durations"].cpu().numpy()
+    for b in range(B):
+        c = counts[b]
+        assert np.array_equal(perms[b, :c], ref["perms"][b, :c]), (which, N, b)
+        assert np.array_equal(dur[b, :c], ref["durations"][b, :c]), (which, N, b)
+        assert (perms[b, c:] == sentinel_p).all() and (dur[b, c:] == sentinel_d).all()    # untouched past count
+    assert np.array_equal(out["residual"].cpu().numpy(), ref["residual"])
+    assert np.array_equal(out["hashes"].cpu().numpy().view(np.uint64), ref["hashes"])
+    if which == "bvn":
+        assert np.array_equal(out["pad_total"].cpu().numpy(), ref["pad_total"])
+    # count/hash-only mode gives the same hashes
+    lean = fn(dev(mats), kmax, zero_diag=zero_diag, want_perms=False, want_residual=False, want_hashes=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(lean["hashes"].cpu().numpy().view(np.uint64), ref["hashes"])
+    assert np.array_equal(lean["counts"].cpu().numpy(), ref["counts"])
+
+
+SHAPES = [(1, 1.0, 10), (2, 1.0, 3), (3, 0.7, 4), (5, 0.6, 2), (8, 1.0, 1000), (16, 0.5, 30), (33, 0.3, 5),
+          (64, 1.0, 100000), (65, 0.4, 9), (100, 0.8, 3), (128, 0.6, 40000)]
+
+
+@pytest.mark.parametrize("N,density,high", SHAPES)
+@pytest.mark.parametrize("zero_diag", [False, True])
+def test_greedy_random(lib, N, density, high, zero_diag):
+    say("greedy random", N, density, high, zero_diag)
+    mats = workloads.random_matrices(6, N, seed=900 + N, density=density, high=high)
+    mats[1] = 0                                                       # an all-zero matrix in the batch
+    for kmax in (3, 2 * N + 2):
+        check_decomposition(lib, "greedy", mats, kmax, zero_diag)
+
+
+@pytest.mark.parametrize("N,density,high", SHAPES)
+@pytest.mark.parametrize("zero_diag", [False, True])
+def test_bvn_random(lib, N, density, high, zero_diag):
+    say("bvn random", N, density, high, zero_diag)
+    nb = 6 if N <= 65 else 2
+    mats = workloads.random_matrices(nb, N, seed=1900 + N, density=density, high=high)
+    mats[1] = 0
+    check_decomposition(lib, "bvn", mats, 5, zero_diag)
+    check_decomposition(lib, "bvn", mats, oracle.bvn_bound(N) if N <= 65 else 600, zero_diag)
+
+
+def test_decompose_special_cases(lib):
+    say("decompose special cases")
+    n = 16
+    eye = np.zeros((3, n, n), dtype=np.int32)
+    eye[0] = np.eye(n, dtype=np.int32)[np.random.default_rng(0).permutation(n)] * 7      # c * P
+    eye[1] = 1                                                                            # all ones
+    eye[2] = np.outer(np.arange(1, n + 1), np.arange(2, n + 2))                           # unique optimum
+    for which in ("greedy", "bvn"):
+        check_decomposition(lib, which, eye, 300, False)
+        check_decomposition(lib, which, eye, 0, False)                                    # kmax = 0
+    big = np.full((1, 8, 8), (1 << 28) - 1, dtype=np.int32)                               # N * max < 2^31
+    check_decomposition(lib, "greedy", big, 20, False)
+    check_decomposition(lib, "bvn", big, 100, False)
+    with pytest.raises(lib.MoeError):
+        lib.moe_decompose_greedy(torch.zeros((1, 129, 129), dtype=torch.int32, device=DEV), 4)
+
+
+def test_decompose_stress_matrices_128(lib):
+    """The batched stress workload at its real shape (128 x 128, Zipf rows), a sample of matrices."""
+    say("decompose stress 128")
+    mats = workloads.stress_matrices(48, 128)
+    check_decomposition(lib, "greedy", mats, 32, True)
+    check_decomposition(lib, "bvn", mats[:8], 512, True)
+    say("decompose stress 128: full BvN on 2 matrices")
+    check_decomposition(lib, "bvn", mats[:2], oracle.bvn_bound(128), True)
+
+
+# ------------------------------------------------------------------------------ slice table
+@pytest.mark.parametrize("name,which", [("tiny", "greedy"), ("tiny", "bvn"), ("c2", "greedy"), ("c2", "bvn"), ("c3", "greedy")])
+def test_slice_table(lib, name, which):
+    say("slice table", name, which)
+    cfg = workloads.CONFIGS[name]
+    ids = workloads.config_routing(cfg)
+    traffic, _ = oracle.route_histogram(ids, cfg.E)
+    order = np.argsort(-traffic.sum(0), kind="stable")
+    kmax = cfg.kmax if which == "greedy" else oracle.bvn_bound(cfg.N)
+    d_ids, d_traffic = dev(ids), dev(traffic)
+    fn = lib.moe_decompose_greedy if which == "greedy" else lib.moe_decompose_bvn
+    sched = fn(d_traffic.unsqueeze(0), kmax, zero_diag=True)
+    if which == "greedy":
+        rp, rd, _ = oracle.decompose_greedy(traffic, kmax, zero_diag=True)
+    else:
+        rp, rd, _, _, _ = oracle.decompose_bvn(traffic, kmax, zero_diag=True)
+    for r in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):
+        off = lib.moe_slice_table(d_ids, cfg.E, r, d_traffic, sched["perms"][0], sched["durations"][0], sched["counts"],
+                                  kmax)
+        torch.cuda.synchronize()
+        ref, _ = oracle.slice_table(ids, cfg.E, r, traffic, rp, rd, kmax, want_rows=False)
+        assert np.array_equal(off.cpu().numpy(), ref), (name, which, r)
+
+
+def test_slice_table_many_windows(lib):
+    """A hand-made schedule that wires one source to the receiver in thousands of matchings
+    (more windows than fit in LDS) and ships one assignment at a time."""
+    say("slice table many windows")
+    N, E, T, topk, r = 4, 8, 6000, 1, 2
+    rng = np.random.default_rng(3)
+    ids = rng.integers(0, E, size=(N, T, topk)).astype(np.int32)
+    traffic, _ = oracle.route_histogram(ids, E)
+    kmax = 3000
+    perms = np.tile(np.array([[r, 0, 1, 3]], dtype=np.uint8), (kmax, 1))      # source 0 -> r in every matching
+    perms[::3] = np.array([1, r, 0, 3], dtype=np.uint8)                       # every third: source 1 -> r
+    dur = rng.integers(0, 3, size=kmax).astype(np.int32)
+    count = np.array([kmax - 5], dtype=np.int32)
+    off = lib.moe_slice_table(dev(ids), E, r, dev(traffic), dev(perms), dev(dur), dev(count), kmax)
+    torch.cuda.synchronize()
+    ref, _ = oracle.slice_table(ids, E, r, traffic, perms[:kmax - 5], dur[:kmax - 5], kmax, want_rows=False)
+    assert np.array_equal(off.cpu().numpy(), ref)
+
+
+# ------------------------------------------------------------------------------ FFN
+def ffn_error(y_gpu_bits, y_ref, offsets, rows=None):
+    """max over (slice, expert) groups of max|y - yref| / max|yref| on the given rows."""
+    y = oracle.decode_bf16(y_gpu_bits)
+    if rows is None:
+        rows = np.arange(int(offsets[-1]))
+    grp = np.searchsorted(offsets, rows, side="right") - 1
+    worst = 0.0
+    for g in np.unique(grp):
+        sel = grp == g
+        scale = np.abs(y_ref[sel]).max()
+        assert scale > 0
+        worst = max(worst, float(np.abs(y[sel] - y_ref[sel]).max() / scale))
+    return worst
+
+
+def upload_weights(W):
+    if W.dtype == "bf16":
+        return dict(w_gate=dev_bf16(W.w_gate), w_up=dev_bf16(W.w_up), w_down=dev_bf16(W.w_down))
+    return dict(w_gate=dev(W.w_gate), w_up=dev(W.w_up), w_down=dev(W.w_down),
+                s_gate=dev(W.s_gate), s_up=dev(W.s_up), s_down=dev(W.s_down))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("tile_rows", ["64", "128", "256"])
+@pytest.mark.parametrize("E_loc,d,f,M,S", [(1, 256, 512, 700, 3), (2, 512, 384, 1500, 4), (4, 256, 128, 333, 5)])
+def test_ffn_small(lib, dtype, tile_rows, E_loc, d, f, M, S):
+    say("ffn small", dtype, tile_rows, E_loc, d, f, M, S)
+    os.environ["MOE_FFN_ROWS"] = tile_rows
+    try:
+        W = workloads.ffn_weights(E_loc, d, f, seed=d + f, dtype=dtype)
+        x = workloads.activations(M + 9, d, seed=M)                                      # 9 spare rows past the last group
+        offsets = workloads.random_offsets(S * E_loc, M, seed=M + S)
+        y0 = torch.full((M + 9, d), 3.0, dtype=torch.bfloat16, device=DEV)
+        y = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(offsets), S, E_loc, y=y0, **upload_weights(W))
+        torch.cuda.synchronize()
+        ref = oracle.expert_ffn_sliced(x, offsets, E_loc, W)
+        yb = host_bf16_bits(y)
+        err = ffn_error(yb[:M], ref, offsets)
+        say("   max relative error", err)
+        assert err <= FFN_TOL[dtype]
+        assert (oracle.decode_bf16(yb[M:]) == 3.0).all()                                  # rows past the end untouched
+        # a row's result does not depend on how the rows are sliced: one slice per expert, same experts
+        expert = (np.searchsorted(offsets, np.arange(M), side="right") - 1) % E_loc
+        order = np.argsort(expert, kind="stable")
+        off2 = np.zeros(E_loc + 1, dtype=np.int32)
+        off2[1:] = np.cumsum(np.bincount(expert, minlength=E_loc))
+        y2 = lib.moe_expert_ffn_sliced(dev_bf16(x[order]), dev(off2), 1, E_loc, **upload_weights(W))
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bf16_bits(y2), yb[:M][order])
+    finally:
+        os.environ.pop("MOE_FFN_ROWS", None)
+
+
+def test_ffn_edge_cases(lib):
+    say("ffn edge cases")
+    E_loc, d, f = 2, 256, 128
+    W = workloads.ffn_weights(E_loc, d, f, seed=1)
+    up = upload_weights(W)
+    x = workloads.activations(64, d, seed=2)
+    # all groups empty: nothing is written
+    y0 = torch.full((64, d), 5.0, dtype=torch.bfloat16, device=DEV)
+    off = np.zeros(2 * E_loc + 1, dtype=np.int32)
+    y = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(off), 2, E_loc, y=y0, **up)
+    torch.cuda.synchronize()
+    assert (y.float() == 5.0).all()
+    # a single row, and a group of exactly one tile plus one row
+    for sizes in ([1, 0, 0, 0], [0, 0, 0, 1], [64, 0, 0, 0][::-1], [33, 31, 0, 0]):
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        y = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(off), 2, E_loc, **up)
+        torch.cuda.synchronize()
+        ref = oracle.expert_ffn_sliced(x, off, E_loc, W)
+        assert ffn_error(host_bf16_bits(y)[:off[-1]], ref, off) <= FFN_TOL["bf16"]
+    with pytest.raises(lib.MoeError):
+        lib.moe_expert_ffn_sliced(dev_bf16(x[:, :128]), dev(off), 2, E_loc, w_gate=up["w_gate"][:, :, :128].contiguous(),
+                                  w_up=up["w_up"][:, :, :128].contiguous(), w_down=up["w_down"][:, :128].contiguous())
+
+
+# ------------------------------------------------------------------------------ whole path, full-size configs
+def run_path(lib, cfg, r, which="greedy", x_seed=0):
+    """histogram -> decomposition -> slice table -> FFN on the GPU; returns everything on the host."""
+    ids = workloads.config_routing(cfg)
+    d_ids = dev(ids)
+    traffic, _ = lib.moe_route_histogram(d_ids, cfg.E)
+    kmax = cfg.kmax if which == "greedy" else oracle.bvn_bound(cfg.N)
+    fn = lib.moe_decompose_greedy if which == "greedy" else lib.moe_decompose_bvn
+    sched = fn(traffic.unsqueeze(0), kmax, zero_diag=True)
+    offsets = lib.moe_slice_table(d_ids, cfg.E, r, traffic, sched["perms"][0], sched["durations"][0], sched["counts"], kmax)
+    torch.cuda.synchronize()
+    M = int(offsets[-1].item())
+    W = workloads.ffn_weights(cfg.E_loc, cfg.d, cfg.f, seed=cfg.seed, dtype=cfg.weight_dtype)
+    x = workloads.activations(M, cfg.d, seed=cfg.seed + x_seed)
+    y = lib.moe_expert_ffn_sliced(dev_bf16(x), offsets, kmax + 2, cfg.E_loc, **upload_weights(W))
+    torch.cuda.synchronize()
+    return dict(ids=ids, traffic=traffic.cpu().numpy(), sched={k: (v.cpu().numpy() if v is not None else None) for k, v in sched.items()},
+                offsets=offsets.cpu().numpy(), M=M, W=W, x=x, y=host_bf16_bits(y), kmax=kmax)
+
+
+def check_path(cfg, r, res, which, n_sample=256):
+    traffic, _ = oracle.route_histogram(res["ids"], cfg.E)
+    assert np.array_equal(res["traffic"], traffic)
+    kmax = res["kmax"]
+    if which == "greedy":
+        rp, rd, rr = oracle.decompose_greedy(traffic, kmax, zero_diag=True)
+    else:
+        rp, rd, rr, _, _ = oracle.decompose_bvn(traffic, kmax, zero_diag=True)
+    c = int(res["sched"]["counts"][0])
+    assert c == len(rd)
+    assert np.array_equal(res["sched"]["perms"][0, :c], rp) and np.array_equal(res["sched"]["durations"][0, :c], rd)
+    assert np.array_equal(res["sched"]["residual"][0], rr)
+    ref_off, _ = oracle.slice_table(res["ids"], cfg.E, r, traffic, rp, rd, kmax, want_rows=False)
+    assert np.array_equal(res["offsets"], ref_off)
+    assert res["M"] == traffic[:, r].sum()
+    # FFN: every non-empty group contributes its first and last rows plus a random sample
+    rng = np.random.default_rng(1)
+    off = res["offsets"].astype(np.int64)
+    rows = []
+    for g in range(len(off) - 1):
+        lo, hi = off[g], off[g + 1]
+        if hi > lo:
+            rows += [lo, hi - 1] + list(rng.integers(lo, hi, size=min(n_sample // 8, hi - lo)))
+    rows = np.unique(np.array(rows, dtype=np.int64))
+    ref = oracle.expert_ffn_sliced(res["x"], off, cfg.E_loc, res["W"], rows=rows)
+    err = ffn_error(res["y"][rows], ref, off, rows=rows)
+    say("   rows", res["M"], "sampled", len(rows), "max relative error", err)
+    assert err <= FFN_TOL[cfg.weight_dtype]
+
+
+@pytest.mark.parametrize("name,which", [("tiny", "greedy"), ("tiny", "bvn"), ("c2", "greedy"), ("c2", "bvn"), ("c3", "greedy")])
+def test_whole_path_full_size(lib, name, which):
+    cfg = workloads.CONFIGS[name]
+    say("whole path", name, which)
+    ids = workloads.config_routing(cfg)
+    traffic, _ = oracle.route_histogram(ids, cfg.E)
+    order = np.argsort(-traffic.sum(0), kind="stable")
+    r = int(order[0]) if name != "c3" else int(order[len(order) // 2])       # hottest rank (median one for the 14336-wide FFN)
+    res = run_path(lib, cfg, r, which)
+    check_path(cfg, r, res, which)
+
+
+def test_whole_path_c4_fp8(lib):
+    """64 ranks, 256 experts, top-8, fp8 block-scaled weights; median-load receiving rank."""
+    cfg = workloads.CONFIGS["c4"]
+    say("whole path c4 fp8")
+    ids = workloads.config_routing(cfg)
+    traffic, _ = oracle.route_histogram(ids, cfg.E)
+    order = np.argsort(-traffic.sum(0), kind="stable")
+    r = int(order[len(order) // 2])
+    res = run_path(lib, cfg, r, "greedy")
+    check_path(cfg, r, res, "greedy", n_sample=128)
