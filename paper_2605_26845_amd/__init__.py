@@ -62,6 +62,9 @@ def load():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise MoeError("libmoecircuit.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # torch ships its own HIP runtime (soname libamdhip64.so.7); importing it first makes the
+    # library bind to that one instead of bringing a second runtime into the process
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     L.moe_route_histogram.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp]

@@ -438,7 +438,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
     {
         int i = 0, j = 0;
         int ri = bcast<NPL>(rdef, 0), cj = bcast<NPL>(cdef, 0);
-        for (int guard = 0; guard < 2 * N + 2 && i < N && j < N; ++guard) {
+        for (int guard = 0; guard < 4 * N + 4 && i < N && j < N; ++guard) {   // <= 2N advances + 2N-1 fills
             if (ri == 0) { ++i; if (i < N) ri = bcast<NPL>(rdef, i); continue; }
             if (cj == 0) { ++j; if (j < N) cj = bcast<NPL>(cdef, j); continue; }
             int dl = min(ri, cj);
