@@ -13,6 +13,7 @@
 // and can store 8 bytes at a time.
 #include "common.hpp"
 #include <stdlib.h>
+#include <type_traits>
 
 namespace {
 
@@ -23,11 +24,10 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
 constexpr int FFN_THREADS = 256;
-constexpr int BK = 64;                 // K slab: 64 bf16 = 128 bytes = 8 chunks of 16 bytes per row
 constexpr int BN = 256;                // tile columns (phase 1: 128 gate + 128 up)
-constexpr int ROW_BYTES = BK * 2;
 constexpr int PLAN_THREADS = 1024;
 constexpr int MAX_GROUPS = 65536;
+constexpr int PLAN_HDR = 5;            // plan[0] = (row blocks, 0, 0, 0); plan[1..2] / plan[3..4] = tile queue counters of phase 1 / 2
 
 struct FfnArgs {
     const __bf16* x;                   // [M][d]
@@ -35,7 +35,7 @@ struct FfnArgs {
     __bf16* y;                         // [M][d]
     const void *wg, *wu, *wd;          // bf16 or fp8 codes
     const float *sg, *su, *sd;         // block scales (fp8) or null
-    const int4* plan;                  // plan[0].x = number of row blocks; plan[1 + i] = (row0, row_end, expert, group)
+    int4* plan;                        // plan[0].x = number of row blocks; plan[PLAN_HDR + i] = (row0, row_end, expert, group)
     int d, f;
 };
 
@@ -70,12 +70,13 @@ void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int 
         for (int w = 0; w < wave; ++w) base += wave_tot[w];
         int start = base + incl - nblk;
         for (int k = 0; k < nblk; ++k)
-            if (start + k < cap) plan[1 + start + k] = make_int4(lo + k * bm, hi, g % e_loc, g);
+            if (start + k < cap) plan[PLAN_HDR + start + k] = make_int4(lo + k * bm, hi, g % e_loc, g);
         __syncthreads();
         if (tid == PLAN_THREADS - 1) running = base + incl;
         __syncthreads();
     }
     if (tid == 0) plan[0] = make_int4(min(running, cap), 0, 0, 0);
+    if (tid >= 1 && tid < PLAN_HDR) plan[tid] = make_int4(0, 0, 0, 0);      // tile queue counters
 }
 
 // ---------------------------------------------------------------------------------- helpers
@@ -110,66 +111,151 @@ __device__ __forceinline__ u32x4 dequant8(u32x2 codes, float scale) {
 // PHASE 1: A = x (K = d), B rows 0..127 = gate rows, 128..255 = up rows of the tile's 128 columns.
 // PHASE 2: A = h (K = f), B rows = 256 rows of w_down.
 // MB = row blocks of 32 per wavefront: BM = 64 * MB.   FP8 = weights are block-scaled E4M3 codes.
-template <int PHASE, int MB, bool FP8>
+//
+// K slabs of 64 are double buffered in LDS.  bf16 operands go global -> LDS directly (each
+// wavefront instruction deposits 64 x 16 bytes contiguously, so the XOR swizzle is applied to
+// the global chunk a lane fetches); fp8 weights pass through registers to be dequantised.
+// Tiles are handed out by eight atomic queues, one per XCD (workgroup id modulo 8), each
+// walking its own chunks of neighbouring tiles so that the workgroups sharing an L2 also share
+// operand slabs; a workgroup whose queue runs dry takes from the others.
+
+struct TileGeom {                      // how tiles are grouped into chunks
+    int nblocks, NT, NCG, CN, RB, nchunks;
+    __device__ __forceinline__ void init(int nblocks_, int NT_) {
+        nblocks = nblocks_; NT = NT_;
+        NCG = (NT + 7) / 8;                        // column groups of at most 8 (11 -> 2 x 6)
+        CN = (NT + NCG - 1) / NCG;
+        RB = 32 / CN < 1 ? 1 : 32 / CN;            // about 32 tiles per chunk
+        nchunks = ((nblocks + RB - 1) / RB) * NCG;
+    }
+    // ticket k of queue x -> tile; returns 1 = valid, 0 = hole in the padded grid, -1 = queue exhausted
+    __device__ __forceinline__ int decode(int x, int k, int& blk, int& nt) const {
+        const int chs = RB * CN;
+        const int c = (k / chs) * 8 + x, j = k % chs;
+        if (c >= nchunks) return -1;
+        blk = (c / NCG) * RB + j / CN;
+        nt = (c % NCG) * CN + j % CN;
+        return (blk < nblocks && nt < NT) ? 1 : 0;
+    }
+};
+
+template <int N> __device__ __forceinline__ void wait_vmcnt();
+template <> __device__ __forceinline__ void wait_vmcnt<0>()  { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<2>()  { asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<4>()  { asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<6>()  { asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<8>()  { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<10>() { asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<12>() { asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<16>() { asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<18>() { asm volatile("s_waitcnt vmcnt(18)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<20>() { asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<24>() { asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<30>() { asm volatile("s_waitcnt vmcnt(30)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<32>() { asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<36>() { asm volatile("s_waitcnt vmcnt(36)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<40>() { asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); }
+template <> __device__ __forceinline__ void wait_vmcnt<48>() { asm volatile("s_waitcnt vmcnt(48)" ::: "memory"); }
+
+// Workgroup barrier that orders LDS traffic only.  (__syncthreads() also drains every outstanding global
+// access, which would serialise the slab copies that are meant to stay in flight across K steps.)
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// BK = K slab width (32 or 64 bf16), NST = LDS stages: slabs kt+1 .. kt+NST-1 are in flight or landed while slab kt
+// is multiplied.
+template <int PHASE, int MB, bool FP8, int BK, int NST>
 __global__ __launch_bounds__(FFN_THREADS)
 void ffn_gemm_kernel(FfnArgs a) {
     constexpr int BM = 64 * MB;
+    constexpr int ROW_BYTES = BK * 2;                  // one slab row
+    constexpr int CPR = BK / 8;                        // 16-byte chunks per row (4 or 8)
+    constexpr int RS = FFN_THREADS / CPR;              // slab rows covered by one pass of the 256 threads (64 or 32)
+    constexpr int KS = BK / 16;                        // MFMA K steps per slab
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
-    constexpr int CA = BM * 8 / FFN_THREADS;          // 16-byte chunks per thread, A slab
-    constexpr int CB = BN * 8 / FFN_THREADS;          // B slab (= 8)
+    constexpr int CA = BM / RS;                        // 16-byte chunks per thread, A slab
+    constexpr int CB = BN / RS;                        // B slab
+    constexpr int ESZ = FP8 ? 1 : 2;
+    constexpr int LPS = CA + (FP8 ? 0 : CB);           // asynchronous copies per thread and slab
+    static_assert(NST >= 2 && NST <= 4 && KS % 2 == 0, "pipeline shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int s_ticket[2];                        // (block, column tile) of the next tile, -1 = none
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l31 = lane & 31, lhi = lane >> 5;
     const int K = PHASE == 1 ? a.d : a.f;
-    const int NT = PHASE == 1 ? a.f / 128 : a.d / BN;
     const int KT = K / BK;
-    const long long total = (long long)a.plan[0].x * NT;
+    TileGeom geom;
+    geom.init(a.plan[0].x, PHASE == 1 ? a.f / 128 : a.d / BN);
+    int* queues = (int*)(a.plan + (PHASE == 1 ? 1 : 3));
+    const int my_xcd = blockIdx.x & 7;
 
-    // staging coordinates of this thread: chunk c = tid + i*256 -> row = row0 + 32*i, 16-byte column kc
-    const int row0 = tid >> 3, kc = tid & 7;
-    const int st_off = row0 * ROW_BYTES + ((kc ^ (row0 & 7)) << 4);
-    // fragment coordinates: row l31 of a 32-row block, chunk (2*ks + lhi), swizzled by (row & 7)
-    int frag_off[4];
+    // LDS layout of a slab: row-major, 16-byte chunk c of row r sits at position c ^ swz(r).  With 64 banks of 4
+    // bytes a 16-lane group of a ds_read_b128 touches 256 bytes; swz makes 16 consecutive rows hit 16 different
+    // 16-byte bank groups: 128-byte rows -> (r >> 1) & 7, 64-byte rows -> (r >> 2) & 3.
+    // Staging: chunk id = tid + i*256 -> row = tid / CPR + i*RS.  One wavefront instruction deposits 64 x 16 bytes
+    // contiguously (whole rows), so the swizzle is applied to the global chunk a lane fetches.
+    const int row0 = tid / CPR;
+    const int swz0 = BK == 64 ? ((row0 >> 1) & 7) : ((row0 >> 2) & 3);     // same for row0 + i*RS
+    const int kcg = (tid % CPR) ^ swz0;
+    const int wave_bytes = wave * 1024;
+    const int st_off = row0 * ROW_BYTES + ((tid % CPR) << 4);    // register path: same position
+    // fragment coordinates: row l31 of a 32-row block, chunk (2*ks + lhi)
+    const int fswz = BK == 64 ? ((l31 >> 1) & 7) : ((l31 >> 2) & 3);
+    int frag_off[KS];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) frag_off[ks] = l31 * ROW_BYTES + ((((ks << 1) | lhi) ^ (lane & 7)) << 4);
+    for (int ks = 0; ks < KS; ++ks) frag_off[ks] = l31 * ROW_BYTES + ((((ks << 1) | lhi) ^ fswz) << 4);
     int brow[4];                                       // first B-slab row of this wave's 4 column blocks
 #pragma unroll
     for (int q = 0; q < 4; ++q) brow[q] = PHASE == 1 ? ((q >> 1) * 128 + wn * 64 + (q & 1) * 32) : (wn * 128 + q * 32);
 
-    // workgroups of one XCD (blockIdx % 8) take neighbouring tiles so that they share slabs in its L2
-    const int grid = gridDim.x;
-    const int slot = (grid % 8 == 0) ? (int)(blockIdx.x % 8) * (grid / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    // thread 0 pulls tickets; own queue first, then the others
+    auto fetch = [&](int first_k) {
+        int q = my_xcd, k = first_k, blk = -1, nt = -1;
+        for (int tries = 0; tries < 8;) {
+            int st = geom.decode(q, k, blk, nt);
+            if (st == 1) break;
+            if (st < 0) { blk = -1; ++tries; q = (q + 1) & 7; }
+            if (tries < 8) k = atomicAdd(&queues[q], 1);
+        }
+        s_ticket[0] = blk; s_ticket[1] = nt;
+    };
+    if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));
+    __syncthreads();
 
-    for (long long item = slot; item < total; item += grid) {
-        const int blk = (int)(item / NT), nt = (int)(item - (long long)blk * NT);
-        const int4 info = a.plan[1 + blk];
+    while (true) {
+        const int blk = s_ticket[0], nt = s_ticket[1];
+        if (blk < 0) break;
+        const int4 info = a.plan[PLAN_HDR + blk];
         const int m0 = info.x, m_end = info.y, e = info.z;
         const int rows = min(BM, m_end - m0);
 
         // ---- per-tile global addressing; rows past the group's end re-read its last row.
-        //      B slab row r = row0 + 32*i: only i selects gate / up / 128-row block, so each B address is a
+        //      B slab row r = row0 + RS*i: only i selects gate / up / 128-row block, so each B address is a
         //      wave-uniform base plus one per-thread byte offset.
         const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
         int a_off[CA];
 #pragma unroll
-        for (int i = 0; i < CA; ++i) a_off[i] = (m0 + min(row0 + 32 * i, rows - 1)) * K + kc * 8;
-        constexpr int ESZ = FP8 ? 1 : 2;
-        const unsigned int b_voff = (unsigned int)(row0 * K + kc * 8) * ESZ;
+        for (int i = 0; i < CA; ++i) a_off[i] = (m0 + min(row0 + RS * i, rows - 1)) * K + kcg * 8;
+        const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
         const unsigned char* bbase[CB];
         const float* sbase[CB];
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
-            long long wrow;                                               // first weight row of this 32-row strip
+            constexpr int PER_HALF = 128 / RS;                            // passes per 128 slab rows
+            long long wrow;                                               // first weight row of this strip
             const void* w;
-            if (PHASE == 1) { wrow = (long long)e * a.f + nt * 128 + 32 * (i & 3); w = (i < 4) ? a.wg : a.wu; }
-            else            { wrow = (long long)e * a.d + nt * BN + 32 * i;        w = a.wd; }
+            if (PHASE == 1) { wrow = (long long)e * a.f + nt * 128 + RS * (i % PER_HALF); w = (i < PER_HALF) ? a.wg : a.wu; }
+            else            { wrow = (long long)e * a.d + nt * BN + RS * i;                 w = a.wd; }
             bbase[i] = (const unsigned char*)w + wrow * K * ESZ;
             if (FP8) {
                 // scale row of the 128 x 128 block holding the strip
-                if (PHASE == 1) sbase[i] = ((i < 4) ? a.sg : a.su) + ((long long)e * (a.f / 128) + nt) * (K / 128);
-                else            sbase[i] = a.sd + ((long long)e * (a.d / 128) + nt * 2 + (i >> 2)) * (K / 128);
+                if (PHASE == 1) sbase[i] = ((i < PER_HALF) ? a.sg : a.su) + ((long long)e * (a.f / 128) + nt) * (K / 128);
+                else            sbase[i] = a.sd + ((long long)e * (a.d / 128) + nt * 2 + i / PER_HALF) * (K / 128);
             } else {
                 sbase[i] = nullptr;
             }
@@ -183,82 +269,177 @@ void ffn_gemm_kernel(FfnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
 
-        u32x4 ra[CA], rb[CB];
-        auto load_slab = [&](int kt) {
-#pragma unroll
-            for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const u32x4*>(Abase + a_off[i] + kt * BK);
-#pragma unroll
-            for (int i = 0; i < CB; ++i) {
-                const unsigned char* src = bbase[i] + (size_t)kt * BK * ESZ + b_voff;
-                if (!FP8) {
-                    rb[i] = *reinterpret_cast<const u32x4*>(src);
-                } else {
-                    u32x2 codes = *reinterpret_cast<const u32x2*>(src);
-                    rb[i] = dequant8(codes, sbase[i][kt >> 1]);
-                }
-            }
-        };
-        auto store_slab = [&](int stage) {
-            unsigned char* sa = smem + stage * STAGE;
+        // asynchronous global -> LDS copies of one slab (A always; B when it is bf16)
+        auto issue_slab = [&](int kt, int stage) {
+            unsigned char* sa = smem + stage * STAGE + wave_bytes;
             unsigned char* sb = sa + A_BYTES;
 #pragma unroll
-            for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(sa + st_off + i * 32 * ROW_BYTES) = ra[i];
+            for (int i = 0; i < CA; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
+                                                 (__attribute__((address_space(3))) void*)(sa + i * RS * ROW_BYTES), 16, 0, 0);
+            if (!FP8) {
 #pragma unroll
-            for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * 32 * ROW_BYTES) = rb[i];
+                for (int i = 0; i < CB; ++i)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(bbase[i] + (size_t)kt * BK * ESZ + b_voff),
+                        (__attribute__((address_space(3))) void*)(sb + i * RS * ROW_BYTES), 16, 0, 0);
+            }
+        };
+        // fp8 weights: codes through registers (one slab ahead), dequantised on the way into LDS
+        u32x2 rb[CB];
+        float rscale[CB];
+        auto load_b_regs = [&](int kt) {
+#pragma unroll
+            for (int i = 0; i < CB; ++i) {
+                rb[i] = *reinterpret_cast<const u32x2*>(bbase[i] + (size_t)kt * BK + b_voff);
+                rscale[i] = sbase[i][(kt * BK) >> 7];
+            }
+        };
+        auto store_b_regs = [&](int stage) {
+            unsigned char* sb = smem + stage * STAGE + A_BYTES;
+#pragma unroll
+            for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * RS * ROW_BYTES) = dequant8(rb[i], rscale[i]);
         };
 
-        load_slab(0);
-        __syncthreads();                 // previous tile's readers are done with stage 0
-        store_slab(0);
-        __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            if (kt + 1 < KT) load_slab(kt + 1);
-            const unsigned char* sa = smem + (kt & 1) * STAGE + (wm * (BM / 2)) * ROW_BYTES;
-            const unsigned char* sb = smem + (kt & 1) * STAGE + A_BYTES;
+        // ---- K loop, software pipelined.  All NST stages are kept busy: the barrier that lets a wavefront read
+        //      slab kt+1 sits before the last MFMA batch of slab kt; by then every wavefront holds all of slab kt
+        //      in registers, so the same barrier frees slab kt's stage for slab kt+NST.
+        auto load_frags = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks) {
+            const unsigned char* sa = smem + stage * STAGE + (wm * (BM / 2)) * ROW_BYTES;
+            const unsigned char* sb = smem + stage * STAGE + A_BYTES;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                bf16x8 wf[4], xf[MB];
+            for (int q = 0; q < 4; ++q) wf[q] = *reinterpret_cast<const bf16x8*>(sb + brow[q] * ROW_BYTES + frag_off[ks]);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) wf[q] = *reinterpret_cast<const bf16x8*>(sb + brow[q] * ROW_BYTES + frag_off[ks]);
+            for (int mb = 0; mb < MB; ++mb) xf[mb] = *reinterpret_cast<const bf16x8*>(sa + mb * 32 * ROW_BYTES + frag_off[ks]);
+        };
+        auto load_frag_one = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks, int i) {
+            const unsigned char* sa = smem + stage * STAGE + (wm * (BM / 2)) * ROW_BYTES;
+            const unsigned char* sb = smem + stage * STAGE + A_BYTES;
+            if (i < 4) wf[i] = *reinterpret_cast<const bf16x8*>(sb + brow[i] * ROW_BYTES + frag_off[ks]);
+            else       xf[i - 4] = *reinterpret_cast<const bf16x8*>(sa + (i - 4) * 32 * ROW_BYTES + frag_off[ks]);
+        };
+        auto issue_one = [&](int kt, int stage, int i) {
+            unsigned char* sa = smem + stage * STAGE + wave_bytes;
+            unsigned char* sb = sa + A_BYTES;
+            if (i < CA)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
+                                                 (__attribute__((address_space(3))) void*)(sa + i * RS * ROW_BYTES), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(bbase[i - CA] + (size_t)kt * BK * ESZ + b_voff),
+                    (__attribute__((address_space(3))) void*)(sb + (i - CA) * RS * ROW_BYTES), 16, 0, 0);
+        };
+        // wait until at most `y` whole slabs of this thread's copies are outstanding (copies complete in order)
+        auto wait_slabs = [&](int y) {
+            if (y >= 3) wait_vmcnt<3 * LPS>(); else if (y == 2) wait_vmcnt<2 * LPS>();
+            else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
+        };
+
+        if (FP8) { load_b_regs(0); store_b_regs(0); if (KT > 1) load_b_regs(1); }
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) xf[mb] = *reinterpret_cast<const bf16x8*>(sa + mb * 32 * ROW_BYTES + frag_off[ks]);
+        for (int j = 0; j < NST; ++j)
+            if (j < KT) issue_slab(j, j);
+        wait_slabs(min(NST - 1, KT - 1));
+        lds_barrier();
+        bf16x8 wf[2][4], xf[2][MB];
+        load_frags(wf[0], xf[0], 0, 0);
+        int next_k = 0;
+
+        // One slab.  ISSUE = a further slab (kt + NST) exists and is fetched; the steady-state body is branch free so
+        // that the scheduler can spread LDS reads and slab copies between the MFMAs (MFMA first: the wait for the
+        // fragments of this batch must not also wait for reads issued for the next one).
+        auto slab = [&](int kt, auto issue_tag) {
+            constexpr bool ISSUE = decltype(issue_tag)::value;
+            const int stage = kt % NST;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                bool copies = false;
+                if (ks + 1 < KS) {
+                    load_frags(wf[nxt], xf[nxt], stage, ks + 1);
+                } else if (ISSUE) {
+                    if (FP8) store_b_regs((kt + 1) % NST);
+                    wait_vmcnt<(NST - 2) * LPS>();                       // slab kt+1 landed; kt+2 .. kt+NST-1 may be in flight
+                    lds_barrier();
+                    if (FP8) load_b_regs(kt + 2);                        // before the copies: waited for first
+                    // fragment reads and slab copies alternate in program order (a copy writes LDS, so the compiler
+                    // keeps it ordered against the reads around it)
+                    constexpr int NF = 4 + MB, NC = CA + (FP8 ? 0 : CB);
+#pragma unroll
+                    for (int i = 0; i < (NF > NC ? NF : NC); ++i) {
+                        if (i < NF) load_frag_one(wf[nxt], xf[nxt], (kt + 1) % NST, 0, i);
+                        if (i < NC) issue_one(kt + NST, stage, i);
+                    }
+                    copies = true;
+                } else if (kt + 1 < KT) {
+                    if (FP8) store_b_regs((kt + 1) % NST);
+                    wait_slabs(min(NST - 2, KT - 2 - kt));
+                    lds_barrier();
+                    load_frags(wf[nxt], xf[nxt], (kt + 1) % NST, 0);
+                    if (FP8 && kt + 2 < KT) load_b_regs(kt + 2);
+                }
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        acc[mb][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[q], xf[mb], acc[mb][q], 0, 0, 0);
+                        acc[mb][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][q], xf[cur][mb], acc[mb][q], 0, 0, 0);
+                if (copies) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // vector memory (slab copy)
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (kt + 1 < KT) store_slab((kt + 1) & 1);
-            __syncthreads();
+        };
+        {
+            int kt = 0;
+            for (; kt + NST < KT; ++kt) slab(kt, std::true_type{});
+            for (; kt < KT; ++kt) slab(kt, std::false_type{});
         }
+        if (tid == 0) next_k = atomicAdd(&queues[my_xcd], 1);           // next ticket; its latency hides behind the epilogue
 
         // ---- epilogue.  acc[mb][q][v]: row m = l31 of row block mb; column n = 8*(v>>2) + 4*lhi + (v&3)
         //      of column block q
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int m = m0 + wm * (BM / 2) + mb * 32 + l31;
-            if (m >= m_end) continue;
-            if (PHASE == 1) {
-                __bf16* out = a.h + (long long)m * a.f + nt * 128 + wn * 64 + 4 * lhi;
+            if (m < m_end) {
+                if (PHASE == 1) {
+                    __bf16* out = a.h + (long long)m * a.f + nt * 128 + wn * 64 + 4 * lhi;
 #pragma unroll
-                for (int q = 0; q < 2; ++q)
+                    for (int q = 0; q < 2; ++q)
 #pragma unroll
-                    for (int vg = 0; vg < 4; ++vg) {
-                        float hv[4];
+                        for (int vg = 0; vg < 4; ++vg) {
+                            float hv[4];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) hv[j] = silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j];
-                        *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
-                    }
-            } else {
-                __bf16* out = a.y + (long long)m * a.d + nt * BN + wn * 128 + 4 * lhi;
+                            for (int j = 0; j < 4; ++j) hv[j] = silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j];
+                            *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
+                        }
+                } else {
+                    __bf16* out = a.y + (long long)m * a.d + nt * BN + wn * 128 + 4 * lhi;
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int vg = 0; vg < 4; ++vg)
-                        *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
-                            pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
+                        for (int vg = 0; vg < 4; ++vg)
+                            *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
+                                pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
         }
+        if (tid == 0) fetch(next_k);
+        lds_barrier();                   // next ticket published; every stage is free again (stores stay in flight)
     }
 }
 
@@ -278,11 +459,17 @@ int num_cus() {
     return g_num_cus;
 }
 
+// slab width and stage count per tile height: 256-row tiles keep four 32-wide slabs (128 KiB),
+// smaller tiles three 64-wide ones
+template <int MB> struct Pipe { static constexpr int BK = 64, NST = 3; };
+template <> struct Pipe<4> { static constexpr int BK = 32, NST = 4; };
+
 template <int PHASE, int MB, bool FP8>
 moe_status launch_gemm(const FfnArgs& a, int grid, hipStream_t s) {
-    constexpr size_t lds = 2 * (size_t)(64 * MB + BN) * ROW_BYTES;
+    constexpr int BK = Pipe<MB>::BK, NST = Pipe<MB>::NST;
+    constexpr size_t lds = (size_t)NST * (64 * MB + BN) * BK * 2;
     static bool attr_done = false;
-    auto kern = ffn_gemm_kernel<PHASE, MB, FP8>;
+    auto kern = ffn_gemm_kernel<PHASE, MB, FP8, BK, NST>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
@@ -304,7 +491,7 @@ moe_status launch_both(const FfnArgs& a, int grid1, int grid2, hipStream_t s) {
 
 extern "C" size_t moe_ffn_workspace_bytes(int M, int d, int f) {
     if (M < 0 || d < 1 || f < 1) return 0;
-    return h_bytes(M, f) + (size_t)(plan_capacity(M) + 1) * sizeof(int4);
+    return h_bytes(M, f) + (size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4);
 }
 
 extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, int S, int E_loc, int d, int f,
