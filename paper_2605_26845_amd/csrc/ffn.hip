@@ -23,7 +23,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
-constexpr int FFN_THREADS = 256;
 constexpr int BN = 256;                // tile columns (phase 1: 128 gate + 128 up)
 constexpr int PLAN_THREADS = 1024;
 constexpr int MAX_GROUPS = 65536;
@@ -140,22 +139,16 @@ struct TileGeom {                      // how tiles are grouped into chunks
 };
 
 template <int N> __device__ __forceinline__ void wait_vmcnt();
-template <> __device__ __forceinline__ void wait_vmcnt<0>()  { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<2>()  { asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<4>()  { asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<6>()  { asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<8>()  { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<10>() { asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<12>() { asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<16>() { asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<18>() { asm volatile("s_waitcnt vmcnt(18)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<20>() { asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<24>() { asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<30>() { asm volatile("s_waitcnt vmcnt(30)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<32>() { asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<36>() { asm volatile("s_waitcnt vmcnt(36)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<40>() { asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); }
-template <> __device__ __forceinline__ void wait_vmcnt<48>() { asm volatile("s_waitcnt vmcnt(48)" ::: "memory"); }
+#define MOE_WAIT_VMCNT(n) template <> __device__ __forceinline__ void wait_vmcnt<n>() { asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory"); }
+MOE_WAIT_VMCNT(0) MOE_WAIT_VMCNT(1) MOE_WAIT_VMCNT(2) MOE_WAIT_VMCNT(3) MOE_WAIT_VMCNT(4) MOE_WAIT_VMCNT(5) MOE_WAIT_VMCNT(6) MOE_WAIT_VMCNT(7) 
+MOE_WAIT_VMCNT(8) MOE_WAIT_VMCNT(9) MOE_WAIT_VMCNT(10) MOE_WAIT_VMCNT(11) MOE_WAIT_VMCNT(12) MOE_WAIT_VMCNT(13) MOE_WAIT_VMCNT(14) MOE_WAIT_VMCNT(15) 
+MOE_WAIT_VMCNT(16) MOE_WAIT_VMCNT(17) MOE_WAIT_VMCNT(18) MOE_WAIT_VMCNT(19) MOE_WAIT_VMCNT(20) MOE_WAIT_VMCNT(21) MOE_WAIT_VMCNT(22) MOE_WAIT_VMCNT(23) 
+MOE_WAIT_VMCNT(24) MOE_WAIT_VMCNT(25) MOE_WAIT_VMCNT(26) MOE_WAIT_VMCNT(27) MOE_WAIT_VMCNT(28) MOE_WAIT_VMCNT(29) MOE_WAIT_VMCNT(30) MOE_WAIT_VMCNT(31) 
+MOE_WAIT_VMCNT(32) MOE_WAIT_VMCNT(33) MOE_WAIT_VMCNT(34) MOE_WAIT_VMCNT(35) MOE_WAIT_VMCNT(36) MOE_WAIT_VMCNT(37) MOE_WAIT_VMCNT(38) MOE_WAIT_VMCNT(39) 
+MOE_WAIT_VMCNT(40) MOE_WAIT_VMCNT(41) MOE_WAIT_VMCNT(42) MOE_WAIT_VMCNT(43) MOE_WAIT_VMCNT(44) MOE_WAIT_VMCNT(45) MOE_WAIT_VMCNT(46) MOE_WAIT_VMCNT(47) 
+MOE_WAIT_VMCNT(48) MOE_WAIT_VMCNT(49) MOE_WAIT_VMCNT(50) MOE_WAIT_VMCNT(51) MOE_WAIT_VMCNT(52) MOE_WAIT_VMCNT(53) MOE_WAIT_VMCNT(54) MOE_WAIT_VMCNT(55) 
+MOE_WAIT_VMCNT(56) MOE_WAIT_VMCNT(57) MOE_WAIT_VMCNT(58) MOE_WAIT_VMCNT(59) MOE_WAIT_VMCNT(60) MOE_WAIT_VMCNT(61) MOE_WAIT_VMCNT(62) MOE_WAIT_VMCNT(63) 
+#undef MOE_WAIT_VMCNT
 
 // Workgroup barrier that orders LDS traffic only.  (__syncthreads() also drains every outstanding global
 // access, which would serialise the slab copies that are meant to stay in flight across K steps.)
@@ -167,20 +160,24 @@ __device__ __forceinline__ void lds_barrier() {
 
 // BK = K slab width (32 or 64 bf16), NST = LDS stages: slabs kt+1 .. kt+NST-1 are in flight or landed while slab kt
 // is multiplied.
-template <int PHASE, int MB, bool FP8, int BK, int NST>
-__global__ __launch_bounds__(FFN_THREADS)
+// WMW = wavefronts along the rows (2 or 4; always 2 along the columns), MB = 32-row blocks per wavefront:
+// BM = 32 * MB * WMW rows per tile, 128 * WMW threads.  Eight wavefronts (two per SIMD) matter because one
+// wavefront can only issue slab copies at a limited rate: with four, the copies, not the MFMAs, set the pace.
+template <int PHASE, int WMW, int MB, bool FP8, int BK, int NST, int PER_CU>
+__global__ __launch_bounds__(WMW * 128, PER_CU)
 void ffn_gemm_kernel(FfnArgs a) {
-    constexpr int BM = 64 * MB;
+    constexpr int FFN_THREADS = WMW * 128;
+    constexpr int BM = 32 * MB * WMW;
     constexpr int ROW_BYTES = BK * 2;                  // one slab row
     constexpr int CPR = BK / 8;                        // 16-byte chunks per row (4 or 8)
-    constexpr int RS = FFN_THREADS / CPR;              // slab rows covered by one pass of the 256 threads (64 or 32)
+    constexpr int RS = FFN_THREADS / CPR;              // slab rows covered by one pass of all threads
     constexpr int KS = BK / 16;                        // MFMA K steps per slab
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
     constexpr int CA = BM / RS;                        // 16-byte chunks per thread, A slab
     constexpr int CB = BN / RS;                        // B slab
     constexpr int ESZ = FP8 ? 1 : 2;
     constexpr int LPS = CA + (FP8 ? 0 : CB);           // asynchronous copies per thread and slab
-    static_assert(NST >= 2 && NST <= 4 && KS % 2 == 0, "pipeline shape");
+    static_assert(NST >= 2 && NST <= 4 && KS % 2 == 0 && 3 * LPS < 64, "pipeline shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int s_ticket[2];                        // (block, column tile) of the next tile, -1 = none
 
@@ -197,7 +194,7 @@ void ffn_gemm_kernel(FfnArgs a) {
     // LDS layout of a slab: row-major, 16-byte chunk c of row r sits at position c ^ swz(r).  With 64 banks of 4
     // bytes a 16-lane group of a ds_read_b128 touches 256 bytes; swz makes 16 consecutive rows hit 16 different
     // 16-byte bank groups: 128-byte rows -> (r >> 1) & 7, 64-byte rows -> (r >> 2) & 3.
-    // Staging: chunk id = tid + i*256 -> row = tid / CPR + i*RS.  One wavefront instruction deposits 64 x 16 bytes
+    // Staging: chunk id = tid + i*threads -> row = tid / CPR + i*RS.  One wavefront instruction deposits 64 x 16 bytes
     // contiguously (whole rows), so the swizzle is applied to the global chunk a lane fetches.
     const int row0 = tid / CPR;
     const int swz0 = BK == 64 ? ((row0 >> 1) & 7) : ((row0 >> 2) & 3);     // same for row0 + i*RS
@@ -305,7 +302,7 @@ void ffn_gemm_kernel(FfnArgs a) {
         //      slab kt+1 sits before the last MFMA batch of slab kt; by then every wavefront holds all of slab kt
         //      in registers, so the same barrier frees slab kt's stage for slab kt+NST.
         auto load_frags = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks) {
-            const unsigned char* sa = smem + stage * STAGE + (wm * (BM / 2)) * ROW_BYTES;
+            const unsigned char* sa = smem + stage * STAGE + (wm * (MB * 32)) * ROW_BYTES;
             const unsigned char* sb = smem + stage * STAGE + A_BYTES;
 #pragma unroll
             for (int q = 0; q < 4; ++q) wf[q] = *reinterpret_cast<const bf16x8*>(sb + brow[q] * ROW_BYTES + frag_off[ks]);
@@ -313,7 +310,7 @@ void ffn_gemm_kernel(FfnArgs a) {
             for (int mb = 0; mb < MB; ++mb) xf[mb] = *reinterpret_cast<const bf16x8*>(sa + mb * 32 * ROW_BYTES + frag_off[ks]);
         };
         auto load_frag_one = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks, int i) {
-            const unsigned char* sa = smem + stage * STAGE + (wm * (BM / 2)) * ROW_BYTES;
+            const unsigned char* sa = smem + stage * STAGE + (wm * (MB * 32)) * ROW_BYTES;
             const unsigned char* sb = smem + stage * STAGE + A_BYTES;
             if (i < 4) wf[i] = *reinterpret_cast<const bf16x8*>(sb + brow[i] * ROW_BYTES + frag_off[ks]);
             else       xf[i - 4] = *reinterpret_cast<const bf16x8*>(sa + (i - 4) * 32 * ROW_BYTES + frag_off[ks]);
@@ -383,21 +380,21 @@ void ffn_gemm_kernel(FfnArgs a) {
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         acc[mb][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][q], xf[cur][mb], acc[mb][q], 0, 0, 0);
+                // issue order: one MFMA, then at most one LDS read and one slab copy, repeated
+                constexpr int NMF = 4 * MB, NFR = 4 + MB, NCP = CA + CB;
                 if (copies) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // vector memory (slab copy)
+                    for (int i = 0; i < (NMF > NFR ? NMF : NFR); ++i) {
+                        if (i < NMF) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                        if (i < NFR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+                        if (i < NCP) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // vector memory (slab copy)
                     }
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int i = 0; i < (NMF > NFR ? NMF : NFR); ++i) {
+                        if (i < NMF) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (i < NFR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     }
-                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -413,7 +410,7 @@ void ffn_gemm_kernel(FfnArgs a) {
         //      of column block q
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int m = m0 + wm * (BM / 2) + mb * 32 + l31;
+            const int m = m0 + wm * (MB * 32) + mb * 32 + l31;
             if (m < m_end) {
                 if (PHASE == 1) {
                     __bf16* out = a.h + (long long)m * a.f + nt * 128 + wn * 64 + 4 * lhi;
@@ -459,32 +456,38 @@ int num_cus() {
     return g_num_cus;
 }
 
-// slab width and stage count per tile height: 256-row tiles keep four 32-wide slabs (128 KiB),
-// smaller tiles three 64-wide ones
-template <int MB> struct Pipe { static constexpr int BK = 64, NST = 3; };
-template <> struct Pipe<4> { static constexpr int BK = 32, NST = 4; };
+// Tile shapes.  ROWS = rows per tile:
+//   256: 8 wavefronts (4 x 2), 64 x 128 per wavefront, four 32-wide slabs of 32 KiB          (1 workgroup per CU)
+//   128: 4 wavefronts (2 x 2), 64 x 128 per wavefront, three 32-wide slabs of 24 KiB         (2 workgroups per CU)
+//    64: 4 wavefronts (2 x 2), 32 x 128 per wavefront, three 32-wide slabs of 20 KiB         (2 workgroups per CU)
+template <int ROWS> struct Shape;
+template <> struct Shape<256> { static constexpr int WMW = 4, MB = 2, BK = 32, NST = 4, PER_CU = 1; };
+template <> struct Shape<128> { static constexpr int WMW = 2, MB = 2, BK = 32, NST = 3, PER_CU = 2; };
+template <> struct Shape<64>  { static constexpr int WMW = 2, MB = 1, BK = 32, NST = 3, PER_CU = 2; };
 
-template <int PHASE, int MB, bool FP8>
-moe_status launch_gemm(const FfnArgs& a, int grid, hipStream_t s) {
-    constexpr int BK = Pipe<MB>::BK, NST = Pipe<MB>::NST;
-    constexpr size_t lds = (size_t)NST * (64 * MB + BN) * BK * 2;
+template <int PHASE, int ROWS, bool FP8>
+moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
+    typedef Shape<ROWS> S;
+    constexpr size_t lds = (size_t)S::NST * (ROWS + BN) * S::BK * 2;
     static bool attr_done = false;
-    auto kern = ffn_gemm_kernel<PHASE, MB, FP8, BK, NST>;
+    auto kern = ffn_gemm_kernel<PHASE, S::WMW, S::MB, FP8, S::BK, S::NST, S::PER_CU>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
         attr_done = true;
     }
+    const long long slots = (long long)num_cus() * S::PER_CU;
+    const int grid = (int)(max_tiles < slots ? max_tiles : slots);
     moe::LaunchScope k(PHASE == 1 ? "ffn_gemm1_kernel" : "ffn_gemm2_kernel", s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(FFN_THREADS), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(S::WMW * 128), lds, s, a);
     return k.done();
 }
 
-template <int MB, bool FP8>
-moe_status launch_both(const FfnArgs& a, int grid1, int grid2, hipStream_t s) {
-    moe_status st = launch_gemm<1, MB, FP8>(a, grid1, s);
+template <int ROWS, bool FP8>
+moe_status launch_both(const FfnArgs& a, long long max_blocks, hipStream_t s) {
+    moe_status st = launch_gemm<1, ROWS, FP8>(a, max_blocks * (a.f / 128), s);
     if (st != MOE_OK) return st;
-    return launch_gemm<2, MB, FP8>(a, grid2, s);
+    return launch_gemm<2, ROWS, FP8>(a, max_blocks * (a.d / BN), s);
 }
 
 }  // namespace
@@ -512,14 +515,13 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
     if (!workspace || workspace_bytes < moe_ffn_workspace_bytes(M, d, f)) return MOE_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
 
-    // rows per wavefront tile: large groups take 256-row tiles, fragmented schedules smaller ones
+    // rows per tile: large groups take 256-row tiles, fragmented schedules smaller ones
     const long long avg = M / G;
-    int mb = avg >= 768 ? 4 : (avg >= 96 ? 2 : 1);
+    int bm = avg >= 768 ? 256 : (avg >= 96 ? 128 : 64);
     if (const char* ov = getenv("MOE_FFN_ROWS")) {
         int v = atoi(ov);
-        if (v == 64) mb = 1; else if (v == 128) mb = 2; else if (v == 256) mb = 4;
+        if (v == 64 || v == 128 || v == 256) bm = v;
     }
-    const int bm = 64 * mb;
 
     FfnArgs a;
     a.x = (const __bf16*)x;
@@ -538,15 +540,12 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
         if (st != MOE_OK) return st;
     }
     const long long max_blocks = M / bm + G;
-    const int cus = num_cus();
-    long long t1 = max_blocks * (f / 128), t2 = max_blocks * (d / BN);
-    const int grid1 = (int)(t1 < cus ? t1 : cus), grid2 = (int)(t2 < cus ? t2 : cus);
     if (fp8) {
-        if (mb == 4) return launch_both<4, true>(a, grid1, grid2, s);
-        if (mb == 2) return launch_both<2, true>(a, grid1, grid2, s);
-        return launch_both<1, true>(a, grid1, grid2, s);
+        if (bm == 256) return launch_both<256, true>(a, max_blocks, s);
+        if (bm == 128) return launch_both<128, true>(a, max_blocks, s);
+        return launch_both<64, true>(a, max_blocks, s);
     }
-    if (mb == 4) return launch_both<4, false>(a, grid1, grid2, s);
-    if (mb == 2) return launch_both<2, false>(a, grid1, grid2, s);
-    return launch_both<1, false>(a, grid1, grid2, s);
+    if (bm == 256) return launch_both<256, false>(a, max_blocks, s);
+    if (bm == 128) return launch_both<128, false>(a, max_blocks, s);
+    return launch_both<64, false>(a, max_blocks, s);
 }
