@@ -49,6 +49,10 @@ __device__ __forceinline__ int wave_sum(int x) {
            __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
 }
 __device__ __forceinline__ unsigned long long ballot64(bool p) { return __ballot(p); }
+// The workgroup is a single wavefront, whose LDS accesses execute in program order: no barrier is needed
+// between a lane's store and another lane's load, only that the compiler keeps that order and that pending
+// LDS traffic has drained.  (__syncthreads() would also wait for every outstanding global store.)
+__device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // lane-distributed arrays: element idx lives in lane idx & 63, slot idx >> 6
 template <int NPL>
@@ -141,10 +145,10 @@ __device__ __forceinline__ void load_matrix(const int32_t* __restrict__ A, int32
     } else {
         for (int x = lane; x < total; x += MOE_WAVE) R[x] = A[x];
     }
-    __syncthreads();
+    lds_fence();
     if (zero_diag) {
         for (int i = lane; i < N; i += MOE_WAVE) R[i * N + i] = 0;
-        __syncthreads();
+        lds_fence();
     }
 }
 __device__ __forceinline__ void store_matrix(const int32_t* R, int32_t* __restrict__ out, int N, int lane) {
@@ -199,33 +203,96 @@ __device__ __forceinline__ void bfs_reach_cols(const int (&p)[NPL], const Mask<N
         reached.w[s] |= ballot64(nr);
     }
 }
-// Re-route along the parents: `row` takes `col`, the previous owner of `col` takes its parent
-// column, ... until the free column `stop_col` has been taken.
+// Re-route along the parents: `row` takes `col`, the previous owner of `col` takes its parent column, ...
+// until a column without an owner has been taken.
 template <int NPL>
-__device__ __forceinline__ void apply_path(int row, int col, int stop_col, int (&sigma)[NPL], int (&p)[NPL],
-                                           const int (&parent)[NPL], int lane, int N) {
+__device__ __forceinline__ void apply_path(int row, int col, int (&sigma)[NPL], int (&p)[NPL], const int (&parent)[NPL],
+                                           int lane, int N) {
     for (int guard = 0; guard <= N; ++guard) {
         int prev_owner = bcast<NPL>(p, col);
         set_at<NPL>(sigma, row, col, lane);
         set_at<NPL>(p, col, row, lane);
-        if (col == stop_col) break;
+        if (prev_owner < 0) break;
         row = prev_owner;
         col = bcast<NPL>(parent, prev_owner);
     }
 }
 
-// Turn the perfect matching (sigma: row -> col, p: col -> row) of the graph `tm` into the
-// lexicographically smallest perfect matching of that graph.
+// Inclusive OR-scan over the 64 lanes of a 32-bit value (GFX9 DPP: row shifts, then row broadcasts).
+__device__ __forceinline__ unsigned int wave_or_scan32(unsigned int v) {
+    v |= (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v |= (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v |= (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v |= (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v |= (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
+    v |= (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_or_scan64(unsigned long long v) {
+    unsigned int lo = wave_or_scan32((unsigned int)v), hi = wave_or_scan32((unsigned int)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// Rows >= first_row that have an allowed column below their current one which is not held by an earlier row.
+// Only those rows can possibly move to a smaller column; all others are skipped by the lexicographic pass.
 template <int NPL>
-__device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, int lane, int (&sigma)[NPL], int (&p)[NPL]) {
-    Mask<NPL> fixed_cols;
-    fixed_cols.clear();
-    for (int i = 0; i < N; ++i) {
-        int cur = bcast<NPL>(sigma, i);
-        Mask<NPL> cand = bcast_mask<NPL>(tm, i) & below<NPL>(cur);
+__device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[NPL], int N, int lane, const int (&sigma)[NPL],
+                                                          int first_row) {
+    // taken[s] = columns held by rows up to and including this lane's row (rows are a permutation: own bit removed below)
+    Mask<NPL> taken[NPL], carry;
+    carry.clear();
 #pragma unroll
-        for (int k = 0; k < NPL; ++k) cand.w[k] &= ~fixed_cols.w[k];
-        if (cand.any()) {
+    for (int s = 0; s < NPL; ++s) {
+        Mask<NPL> own;
+        own.clear();
+        if (lane + 64 * s < N) own.set(sigma[s]);
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+            taken[s].w[k] = wave_or_scan64(own.w[k]) | carry.w[k];
+        }
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+            unsigned int lo = (unsigned int)__builtin_amdgcn_readlane((int)(taken[s].w[k] & 0xFFFFFFFFULL), 63);
+            unsigned int hi = (unsigned int)__builtin_amdgcn_readlane((int)(taken[s].w[k] >> 32), 63);
+            carry.w[k] = ((unsigned long long)hi << 32) | lo;
+        }
+    }
+    Mask<NPL> need;
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) {
+        const int row = lane + 64 * s;
+        bool want = false;
+        if (row < N && row >= first_row) {
+            Mask<NPL> c = tm[s] & below<NPL>(sigma[s]);
+#pragma unroll
+            for (int k = 0; k < NPL; ++k) c.w[k] &= ~taken[s].w[k];      // own column is not below itself, so its bit is harmless
+            want = c.any();
+        }
+        need.w[s] = ballot64(want);
+    }
+    return need;
+}
+
+// Turn the perfect matching (sigma: row -> col, p: col -> row) of the graph `tm` into the
+// lexicographically smallest perfect matching of that graph, rows < first_row being final already.  Rows are
+// settled in ascending order; a row can
+// only improve if it has a candidate column (see above), and for such a row one breadth-first search over
+// alternating paths through later rows tells which columns can be vacated for it.
+template <int NPL>
+__device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, int lane, int (&sigma)[NPL], int (&p)[NPL],
+                                             int first_row) {
+    for (int round = 0; round <= N; ++round) {
+        Mask<NPL> need = rows_with_candidates<NPL>(tm, N, lane, sigma, first_row);
+        bool changed = false;
+        while (need.any() && !changed) {
+            const int i = need.first();
+            need.reset(i);
+            int cur = bcast<NPL>(sigma, i);
+            // columns of rows < i are fixed
+            Mask<NPL> cand = bcast_mask<NPL>(tm, i) & below<NPL>(cur);
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) cand.w[s] &= ~ballot64(lane + 64 * s < N && p[s] >= 0 && p[s] < i);
+            if (!cand.any()) continue;
             // which columns can be vacated by re-routing rows > i, the column `cur` being free?
             Mask<NPL> reached;
             reached.clear();
@@ -243,12 +310,13 @@ __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, 
             }
             Mask<NPL> hit = cand & reached;
             if (hit.any()) {
-                int j = hit.first();
-                apply_path<NPL>(i, j, cur, sigma, p, parent, lane, N);
-                cur = j;
+                set_at<NPL>(p, cur, -1, lane);           // row i gives up its column ...
+                apply_path<NPL>(i, hit.first(), sigma, p, parent, lane, N);     // ... and the re-routing ends by taking it
+                changed = true;                  // later rows moved: their candidate sets must be recomputed
+                first_row = i + 1;
             }
         }
-        fixed_cols.set(cur);
+        if (!changed) break;
     }
 }
 
@@ -312,8 +380,30 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
     while (t < kmax && nnz > 0) {
 #pragma unroll
         for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
-        // ---- maximum-weight perfect matching: one shortest augmenting path per row
+        // ---- row reduction: lower u_r until row r has a tight edge, and take that edge if its column is free.
+        //      (Duals stay feasible, matched edges are tight; most rows are settled here and skip the search.)
         for (int r = 0; r < N; ++r) {
+            const int ur = bcast<NPL>(u, r);
+            int slack[NPL], local = INT_MAX;
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) {
+                int j = lane + 64 * s;
+                slack[s] = j < N ? ur + v[s] - R[r * N + j] : INT_MAX;
+                local = min(local, slack[s]);
+            }
+            const int m = wave_min(local);
+            set_at<NPL>(u, r, ur - m, lane);
+            int pick = -1;
+#pragma unroll
+            for (int s = NPL - 1; s >= 0; --s) {
+                unsigned long long f = ballot64(slack[s] == m && p[s] < 0 && lane + 64 * s < N);
+                if (f) pick = 64 * s + __builtin_ctzll(f);
+            }
+            if (pick >= 0) { set_at<NPL>(p, pick, r, lane); set_at<NPL>(sigma, r, pick, lane); }
+        }
+        // ---- maximum-weight perfect matching: one shortest augmenting path per row still unmatched
+        for (int r = 0; r < N; ++r) {
+            if (bcast<NPL>(sigma, r) >= 0) continue;
             int minv[NPL], way[NPL];
             bool used[NPL], intree[NPL];
 #pragma unroll
@@ -375,7 +465,7 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             for (int s = 0; s < NPL; ++s) vv[s] = v[s];
             build_masks<NPL>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
         }
-        lex_smallest<NPL>(tm, N, lane, sigma, p);
+        lex_smallest<NPL>(tm, N, lane, sigma, p, 0);
         // ---- ship whole entries; the matching lasts as long as its heaviest pair
         int dmax = 0, pos = 0;
 #pragma unroll
@@ -388,7 +478,7 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
         }
         dmax = wave_max(dmax);
         nnz -= pos;
-        __syncthreads();
+        lds_fence();
         emit_matching<NPL>(sigma, dmax, N, lane, t, perms_b, dur_b, hashes ? &fnv : nullptr);
         ++t;
     }
@@ -445,7 +535,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
             if (lane == 0) R[i * N + j] += dl;
             ri -= dl; cj -= dl;
         }
-        __syncthreads();
+        lds_fence();
     }
 
     // ---- support masks and number of positive entries
@@ -469,35 +559,71 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
     int t = 0;
     bool broken = false;
     while (t < kmax && nnz > 0 && !broken) {
-        // ---- repair: every free column looks for an unmatched row along an alternating path
-        Mask<NPL> free_cols;
+        // ---- repair, in ascending order of the unmatched rows: row i takes the smallest allowed column that can be
+        //      vacated (or is free) by re-routing matched rows > i only.  Rows < i are untouched, so the previous
+        //      lexicographically smallest matching stays valid above the first repaired row.
+        int first_row = N;
+        bool restricted_ok = true;
+        {
+            Mask<NPL> unmatched;
 #pragma unroll
-        for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
-        while (free_cols.any() && !broken) {
-            const int cf = free_cols.first();
-            free_cols.reset(cf);
-            Mask<NPL> reached;
-            reached.clear();
-            reached.set(cf);
-            bool visited[NPL];
-            int parent[NPL];
+            for (int s = 0; s < NPL; ++s) unmatched.w[s] = ballot64(lane + 64 * s < N && sigma[s] < 0);
+            while (unmatched.any() && restricted_ok) {
+                const int i = unmatched.first();
+                unmatched.reset(i);
+                first_row = min(first_row, i);
+                Mask<NPL> reached;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
-            int target_row = -1;
-            for (int level = 0; level <= N; ++level) {
-                Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, -1, visited, parent);
-                if (!vm.any()) break;
-                Mask<NPL> um;                    // newly visited rows that are unmatched
+                for (int s = 0; s < NPL; ++s) reached.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+                bool visited[NPL];
+                int parent[NPL];
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) um.w[s] = vm.w[s] & ballot64(sigma[s] < 0);
-                if (um.any()) { target_row = um.first(); break; }
-                bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                const Mask<NPL> allowed = bcast_mask<NPL>(tm, i);
+                const int best = allowed.any() ? allowed.first() : -1;
+                for (int level = 0; level <= N; ++level) {
+                    if (best >= 0 && reached.test(best)) break;
+                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, i, visited, parent);
+                    if (!vm.any()) break;
+                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                }
+                Mask<NPL> hit = allowed & reached;
+                if (hit.any()) apply_path<NPL>(i, hit.first(), sigma, p, parent, lane, N);
+                else restricted_ok = false;
             }
-            if (target_row < 0) { broken = true; break; }     // impossible for equal line sums
-            apply_path<NPL>(target_row, bcast<NPL>(parent, target_row), cf, sigma, p, parent, lane, N);
+        }
+        if (!restricted_ok) {
+            // general repair: every free column looks for an unmatched row along an alternating path through any rows
+            first_row = 0;
+            Mask<NPL> free_cols;
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+            while (free_cols.any() && !broken) {
+                const int cf = free_cols.first();
+                free_cols.reset(cf);
+                Mask<NPL> reached;
+                reached.clear();
+                reached.set(cf);
+                bool visited[NPL];
+                int parent[NPL];
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                int target_row = -1;
+                for (int level = 0; level <= N; ++level) {
+                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, -1, visited, parent);
+                    if (!vm.any()) break;
+                    Mask<NPL> um;                    // newly visited rows that are unmatched
+#pragma unroll
+                    for (int s = 0; s < NPL; ++s) um.w[s] = vm.w[s] & ballot64(sigma[s] < 0);
+                    if (um.any()) { target_row = um.first(); break; }
+                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                }
+                if (target_row < 0) { broken = true; break; }     // impossible for equal line sums
+                apply_path<NPL>(target_row, bcast<NPL>(parent, target_row), sigma, p, parent, lane, N);
+            }
         }
         if (broken) break;
-        lex_smallest<NPL>(tm, N, lane, sigma, p);
+        lex_smallest<NPL>(tm, N, lane, sigma, p, first_row < N ? (restricted_ok ? first_row + 1 : 0) : N);
         // ---- coefficient = smallest entry on the matching; subtract it
         int x[NPL], lmin = INT_MAX;
 #pragma unroll
@@ -527,7 +653,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
             nnz -= __popcll(dead_rows.w[s]);
             if (p[s] >= 0 && dead_rows.test(p[s])) p[s] = -1;
         }
-        __syncthreads();
+        lds_fence();
     }
     if (lane == 0) {
         counts[b] = broken ? -1 : t;
