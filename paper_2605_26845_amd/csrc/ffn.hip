@@ -223,24 +223,24 @@ void ffn_gemm_kernel(FfnArgs a) {
     };
     if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));
     __syncthreads();
+    if (s_ticket[0] < 0) return;
 
-    while (true) {
-        const int blk = s_ticket[0], nt = s_ticket[1];
-        if (blk < 0) break;
+    // ---- per-tile state (set by setup()): global addressing of the slab copies; rows past the group's end re-read
+    //      its last row.  B slab row r = row0 + RS*i: only i selects gate / up / 128-row block, so each B address is
+    //      a wave-uniform base plus one per-thread byte offset.
+    const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
+    const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
+    int m0 = 0, m_end = 0, nt = 0;
+    int a_off[CA];
+    const unsigned char* bbase[CB];
+    const float* sbase[CB];
+    auto setup = [&](int blk, int nt_) {
         const int4 info = a.plan[PLAN_HDR + blk];
-        const int m0 = info.x, m_end = info.y, e = info.z;
+        m0 = info.x; m_end = info.y; nt = nt_;
+        const int e = info.z;
         const int rows = min(BM, m_end - m0);
-
-        // ---- per-tile global addressing; rows past the group's end re-read its last row.
-        //      B slab row r = row0 + RS*i: only i selects gate / up / 128-row block, so each B address is a
-        //      wave-uniform base plus one per-thread byte offset.
-        const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
-        int a_off[CA];
 #pragma unroll
         for (int i = 0; i < CA; ++i) a_off[i] = (m0 + min(row0 + RS * i, rows - 1)) * K + kcg * 8;
-        const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
-        const unsigned char* bbase[CB];
-        const float* sbase[CB];
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
             constexpr int PER_HALF = 128 / RS;                            // passes per 128 slab rows
@@ -257,7 +257,85 @@ void ffn_gemm_kernel(FfnArgs a) {
                 sbase[i] = nullptr;
             }
         }
+    };
 
+    // asynchronous global -> LDS copies of one slab (A always; B when it is bf16)
+    auto issue_slab = [&](int kt, int stage) {
+        unsigned char* sa = smem + stage * STAGE + wave_bytes;
+        unsigned char* sb = sa + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < CA; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
+                                             (__attribute__((address_space(3))) void*)(sa + i * RS * ROW_BYTES), 16, 0, 0);
+        if (!FP8) {
+#pragma unroll
+            for (int i = 0; i < CB; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(bbase[i] + (size_t)kt * BK * ESZ + b_voff),
+                    (__attribute__((address_space(3))) void*)(sb + i * RS * ROW_BYTES), 16, 0, 0);
+        }
+    };
+    // fp8 weights: codes through registers (one slab ahead), dequantised on the way into LDS
+    u32x2 rb[CB];
+    float rscale[CB];
+    auto load_b_regs = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            rb[i] = *reinterpret_cast<const u32x2*>(bbase[i] + (size_t)kt * BK + b_voff);
+            rscale[i] = sbase[i][(kt * BK) >> 7];
+        }
+    };
+    auto store_b_regs = [&](int stage) {
+        unsigned char* sb = smem + stage * STAGE + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * RS * ROW_BYTES) = dequant8(rb[i], rscale[i]);
+    };
+
+    // ---- K loop, software pipelined.  All NST stages are kept busy: the barrier that lets a wavefront read
+    //      slab kt+1 sits before the last MFMA batch of slab kt; by then every wavefront holds all of slab kt
+    //      in registers, so the same barrier frees slab kt's stage for slab kt+NST.
+    auto load_frags = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks) {
+        const unsigned char* sa = smem + stage * STAGE + (wm * (MB * 32)) * ROW_BYTES;
+        const unsigned char* sb = smem + stage * STAGE + A_BYTES;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) wf[q] = *reinterpret_cast<const bf16x8*>(sb + brow[q] * ROW_BYTES + frag_off[ks]);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) xf[mb] = *reinterpret_cast<const bf16x8*>(sa + mb * 32 * ROW_BYTES + frag_off[ks]);
+    };
+    auto load_frag_one = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks, int i) {
+        const unsigned char* sa = smem + stage * STAGE + (wm * (MB * 32)) * ROW_BYTES;
+        const unsigned char* sb = smem + stage * STAGE + A_BYTES;
+        if (i < 4) wf[i] = *reinterpret_cast<const bf16x8*>(sb + brow[i] * ROW_BYTES + frag_off[ks]);
+        else       xf[i - 4] = *reinterpret_cast<const bf16x8*>(sa + (i - 4) * 32 * ROW_BYTES + frag_off[ks]);
+    };
+    auto issue_one = [&](int kt, int stage, int i) {
+        unsigned char* sa = smem + stage * STAGE + wave_bytes;
+        unsigned char* sb = sa + A_BYTES;
+        if (i < CA)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
+                                             (__attribute__((address_space(3))) void*)(sa + i * RS * ROW_BYTES), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(bbase[i - CA] + (size_t)kt * BK * ESZ + b_voff),
+                (__attribute__((address_space(3))) void*)(sb + (i - CA) * RS * ROW_BYTES), 16, 0, 0);
+    };
+    // wait until at most `y` whole slabs of this thread's copies are outstanding (copies complete in order)
+    auto wait_slabs = [&](int y) {
+        if (y >= 3) wait_vmcnt<3 * LPS>(); else if (y == 2) wait_vmcnt<2 * LPS>();
+        else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
+    };
+
+    // first slabs of a tile (all stages must be free)
+    auto prologue = [&]() {
+        if (FP8) { load_b_regs(0); store_b_regs(0); if (KT > 1) load_b_regs(1); }
+#pragma unroll
+        for (int j = 0; j < NST; ++j)
+            if (j < KT) issue_slab(j, j);
+    };
+
+    setup(s_ticket[0], s_ticket[1]);
+    prologue();
+    while (true) {
         f32x16 acc[MB][4];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -266,81 +344,11 @@ void ffn_gemm_kernel(FfnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
 
-        // asynchronous global -> LDS copies of one slab (A always; B when it is bf16)
-        auto issue_slab = [&](int kt, int stage) {
-            unsigned char* sa = smem + stage * STAGE + wave_bytes;
-            unsigned char* sb = sa + A_BYTES;
-#pragma unroll
-            for (int i = 0; i < CA; ++i)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
-                                                 (__attribute__((address_space(3))) void*)(sa + i * RS * ROW_BYTES), 16, 0, 0);
-            if (!FP8) {
-#pragma unroll
-                for (int i = 0; i < CB; ++i)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(bbase[i] + (size_t)kt * BK * ESZ + b_voff),
-                        (__attribute__((address_space(3))) void*)(sb + i * RS * ROW_BYTES), 16, 0, 0);
-            }
-        };
-        // fp8 weights: codes through registers (one slab ahead), dequantised on the way into LDS
-        u32x2 rb[CB];
-        float rscale[CB];
-        auto load_b_regs = [&](int kt) {
-#pragma unroll
-            for (int i = 0; i < CB; ++i) {
-                rb[i] = *reinterpret_cast<const u32x2*>(bbase[i] + (size_t)kt * BK + b_voff);
-                rscale[i] = sbase[i][(kt * BK) >> 7];
-            }
-        };
-        auto store_b_regs = [&](int stage) {
-            unsigned char* sb = smem + stage * STAGE + A_BYTES;
-#pragma unroll
-            for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * RS * ROW_BYTES) = dequant8(rb[i], rscale[i]);
-        };
-
-        // ---- K loop, software pipelined.  All NST stages are kept busy: the barrier that lets a wavefront read
-        //      slab kt+1 sits before the last MFMA batch of slab kt; by then every wavefront holds all of slab kt
-        //      in registers, so the same barrier frees slab kt's stage for slab kt+NST.
-        auto load_frags = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks) {
-            const unsigned char* sa = smem + stage * STAGE + (wm * (MB * 32)) * ROW_BYTES;
-            const unsigned char* sb = smem + stage * STAGE + A_BYTES;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) wf[q] = *reinterpret_cast<const bf16x8*>(sb + brow[q] * ROW_BYTES + frag_off[ks]);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) xf[mb] = *reinterpret_cast<const bf16x8*>(sa + mb * 32 * ROW_BYTES + frag_off[ks]);
-        };
-        auto load_frag_one = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks, int i) {
-            const unsigned char* sa = smem + stage * STAGE + (wm * (MB * 32)) * ROW_BYTES;
-            const unsigned char* sb = smem + stage * STAGE + A_BYTES;
-            if (i < 4) wf[i] = *reinterpret_cast<const bf16x8*>(sb + brow[i] * ROW_BYTES + frag_off[ks]);
-            else       xf[i - 4] = *reinterpret_cast<const bf16x8*>(sa + (i - 4) * 32 * ROW_BYTES + frag_off[ks]);
-        };
-        auto issue_one = [&](int kt, int stage, int i) {
-            unsigned char* sa = smem + stage * STAGE + wave_bytes;
-            unsigned char* sb = sa + A_BYTES;
-            if (i < CA)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
-                                                 (__attribute__((address_space(3))) void*)(sa + i * RS * ROW_BYTES), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(bbase[i - CA] + (size_t)kt * BK * ESZ + b_voff),
-                    (__attribute__((address_space(3))) void*)(sb + (i - CA) * RS * ROW_BYTES), 16, 0, 0);
-        };
-        // wait until at most `y` whole slabs of this thread's copies are outstanding (copies complete in order)
-        auto wait_slabs = [&](int y) {
-            if (y >= 3) wait_vmcnt<3 * LPS>(); else if (y == 2) wait_vmcnt<2 * LPS>();
-            else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
-        };
-
-        if (FP8) { load_b_regs(0); store_b_regs(0); if (KT > 1) load_b_regs(1); }
-#pragma unroll
-        for (int j = 0; j < NST; ++j)
-            if (j < KT) issue_slab(j, j);
         wait_slabs(min(NST - 1, KT - 1));
-        lds_barrier();
+        lds_barrier();                   // slab 0 of this tile is in LDS; everybody has read the ticket of this tile
+        if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));             // ticket of the next tile
         bf16x8 wf[2][4], xf[2][MB];
         load_frags(wf[0], xf[0], 0, 0);
-        int next_k = 0;
 
         // One slab.  ISSUE = a further slab (kt + NST) exists and is fetched; the steady-state body is branch free so
         // that the scheduler can spread LDS reads and slab copies between the MFMAs (MFMA first: the wait for the
@@ -404,16 +412,20 @@ void ffn_gemm_kernel(FfnArgs a) {
             for (; kt + NST < KT; ++kt) slab(kt, std::true_type{});
             for (; kt < KT; ++kt) slab(kt, std::false_type{});
         }
-        if (tid == 0) next_k = atomicAdd(&queues[my_xcd], 1);           // next ticket; its latency hides behind the epilogue
+        lds_barrier();                   // every fragment is in registers: all stages are free; next ticket visible
+        const int em0 = m0, em_end = m_end, ent = nt;
+        const int nblk = s_ticket[0], nnt = s_ticket[1];
+        if (nblk >= 0) { setup(nblk, nnt); prologue(); }                // the next tile's first slabs fly during the epilogue
+
 
         // ---- epilogue.  acc[mb][q][v]: row m = l31 of row block mb; column n = 8*(v>>2) + 4*lhi + (v&3)
         //      of column block q
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int m = m0 + wm * (MB * 32) + mb * 32 + l31;
-            if (m < m_end) {
+            const int m = em0 + wm * (MB * 32) + mb * 32 + l31;
+            if (m < em_end) {
                 if (PHASE == 1) {
-                    __bf16* out = a.h + (long long)m * a.f + nt * 128 + wn * 64 + 4 * lhi;
+                    __bf16* out = a.h + (long long)m * a.f + ent * 128 + wn * 64 + 4 * lhi;
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -424,7 +436,7 @@ void ffn_gemm_kernel(FfnArgs a) {
                             *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
                         }
                 } else {
-                    __bf16* out = a.y + (long long)m * a.d + nt * BN + wn * 128 + 4 * lhi;
+                    __bf16* out = a.y + (long long)m * a.d + ent * BN + wn * 128 + 4 * lhi;
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -435,8 +447,7 @@ void ffn_gemm_kernel(FfnArgs a) {
             }
             __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
         }
-        if (tid == 0) fetch(next_k);
-        lds_barrier();                   // next ticket published; every stage is free again (stores stay in flight)
+        if (nblk < 0) break;
     }
 }
 
