@@ -34,7 +34,7 @@ struct FfnArgs {
     __bf16* y;                         // [M][d]
     const void *wg, *wu, *wd;          // bf16 or fp8 codes
     const float *sg, *su, *sd;         // block scales (fp8) or null
-    int4* plan;                        // plan[0].x = number of row blocks; plan[PLAN_HDR + i] = (row0, row_end, expert, group)
+    int4* plan;                        // plan[0].x = number of row blocks; plan[PLAN_HDR + i] = (row0, row_end, expert, class)
     int d, f;
 };
 
@@ -44,6 +44,7 @@ struct FfnArgs {
 // entries beyond `cap` are dropped.
 __global__ __launch_bounds__(PLAN_THREADS)
 void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int M, int bm, int cap, int4* __restrict__ plan) {
+    // plan entry = (first row, end of the group, local expert, shape class of the block: 0 for > 128 rows, 1 for > 64, else 2)
     __shared__ int wave_tot[PLAN_THREADS / 64];
     __shared__ int running;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,7 +70,10 @@ void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int 
         for (int w = 0; w < wave; ++w) base += wave_tot[w];
         int start = base + incl - nblk;
         for (int k = 0; k < nblk; ++k)
-            if (start + k < cap) plan[PLAN_HDR + start + k] = make_int4(lo + k * bm, hi, g % e_loc, g);
+            if (start + k < cap) {
+                const int left = hi - (lo + k * bm);
+                plan[PLAN_HDR + start + k] = make_int4(lo + k * bm, hi, g % e_loc, left > 128 ? 0 : (left > 64 ? 1 : 2));
+            }
         __syncthreads();
         if (tid == PLAN_THREADS - 1) running = base + incl;
         __syncthreads();
@@ -451,6 +455,297 @@ void ffn_gemm_kernel(FfnArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------- adaptive-shape GEMM kernel
+// Same pipeline as above with 8 wavefronts of 64 x 128 each, but the arrangement of the wavefronts is chosen per
+// row block so that ragged slices do not pay for 256 rows they do not have:
+//   class 0: 4 x 2 wavefronts = 256 rows x 256 columns   (4 stages of 32 KiB)
+//   class 1: 2 x 4            = 128 rows x 512 columns   (3 stages of 40 KiB)
+//   class 2: 1 x 8            =  64 rows x 1024 columns  (2 stages of 68 KiB)
+// Every class runs the same number of MFMAs per tile; a block of <= 64 rows needs a quarter of the tiles of class 0.
+// Columns come in units (phase 1: 128 hidden units = 128 gate + 128 up rows; phase 2: 256 rows of w_down); a tile of
+// class c covers 1 / 2 / 4 consecutive units.  A unit past the end is fetched as the last valid one and not stored.
+template <int WMW> struct Cls {
+    static constexpr int WNW = 8 / WMW, U = WNW / 2;
+    static constexpr int BMc = 64 * WMW, BNc = 128 * WNW;
+    static constexpr int A_BYTES = BMc * 64, B_BYTES = BNc * 64, STAGE = A_BYTES + B_BYTES;
+    static constexpr int NST = WMW == 4 ? 4 : (WMW == 2 ? 3 : 2);
+    static constexpr int CA = WMW >= 2 ? WMW / 2 : 1;          // WMW == 1: only the first 4 wavefronts copy A rows
+    static constexpr int CB = WNW;
+    static constexpr int ID = WMW == 4 ? 0 : (WMW == 2 ? 1 : 2);
+};
+constexpr int ADAPTIVE_LDS = 2 * Cls<1>::STAGE;                // 136 KiB >= 4 * 32 KiB, 3 * 40 KiB
+
+template <int PHASE, bool FP8>
+__global__ __launch_bounds__(512, 1)
+void ffn_adaptive_kernel(FfnArgs a) {
+    constexpr int BK = 32, ROW_BYTES = 64, KS = 2, MB = 2, ESZ = FP8 ? 1 : 2;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int s_ticket[3];                        // (block, tile index, class) of the next tile; block -1 = none
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l31 = lane & 31, lhi = lane >> 5;
+    const int K = PHASE == 1 ? a.d : a.f;
+    const int KT = K / BK;
+    const int NU = PHASE == 1 ? a.f / 128 : a.d / 256;          // column units
+    TileGeom geom;
+    geom.init(a.plan[0].x, NU);
+    int* queues = (int*)(a.plan + (PHASE == 1 ? 1 : 3));
+    const int my_xcd = blockIdx.x & 7;
+
+    // slab layout and swizzle as in ffn_gemm_kernel (64-byte rows): chunk id = tid + i*512 -> row = tid/4 + 128*i
+    const int row0 = tid >> 2;
+    const int kcg = (tid & 3) ^ ((row0 >> 2) & 3);
+    const int wave_bytes = wave * 1024;
+    const int st_off = row0 * ROW_BYTES + ((tid & 3) << 4);
+    const int fswz = (l31 >> 2) & 3;
+    int frag_off[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) frag_off[ks] = l31 * ROW_BYTES + ((((ks << 1) | lhi) ^ fswz) << 4);
+
+    // thread 0 pulls tickets (own queue first, then the others).  A ticket names (block, unit); it is a tile only if
+    // the unit is the first of the tile its block's class makes of it.
+    auto fetch = [&](int first_k) {
+        int q = my_xcd, k = first_k, blk = -1, unit = -1, cls = 0;
+        for (int tries = 0; tries < 8;) {
+            int st = geom.decode(q, k, blk, unit);
+            if (st == 1) {
+                cls = a.plan[PLAN_HDR + blk].w;
+                if ((unit & ((1 << cls) - 1)) == 0) break;
+            }
+            if (st < 0) { ++tries; q = (q + 1) & 7; }
+            blk = -1;
+            if (tries < 8) k = atomicAdd(&queues[q], 1);
+        }
+        s_ticket[0] = blk; s_ticket[1] = blk >= 0 ? (unit >> cls) : 0; s_ticket[2] = cls;
+    };
+    if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));
+    __syncthreads();
+    if (s_ticket[0] < 0) return;
+
+    // ---- per-tile copy state
+    const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
+    const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
+    int m0 = 0, m_end = 0, nt = 0;
+    int a_off[2];
+    const unsigned char* bbase[8];
+    const float* sbase[8];
+    u32x2 rb[8];
+    float rscale[8];
+
+    auto setup = [&](auto tag, int blk, int nt_) {
+        typedef Cls<decltype(tag)::value> C;
+        const int4 info = a.plan[PLAN_HDR + blk];
+        m0 = info.x; m_end = info.y; nt = nt_;
+        const int e = info.z;
+        const int rows = min(C::BMc, m_end - m0);
+#pragma unroll
+        for (int i = 0; i < C::CA; ++i) a_off[i] = (m0 + min(row0 + 128 * i, rows - 1)) * K + kcg * 8;
+#pragma unroll
+        for (int i = 0; i < C::CB; ++i) {                                 // 128-row strips of the B slab
+            const int ug = min(nt * C::U + (i >> 1), NU - 1);
+            long long wrow;
+            const void* w;
+            if (PHASE == 1) { wrow = (long long)e * a.f + ug * 128;               w = (i & 1) ? a.wu : a.wg; }
+            else            { wrow = (long long)e * a.d + ug * 256 + (i & 1) * 128; w = a.wd; }
+            bbase[i] = (const unsigned char*)w + wrow * K * ESZ;
+            if (FP8) {
+                if (PHASE == 1) sbase[i] = ((i & 1) ? a.su : a.sg) + ((long long)e * (a.f / 128) + ug) * (K / 128);
+                else            sbase[i] = a.sd + ((long long)e * (a.d / 128) + ug * 2 + (i & 1)) * (K / 128);
+            } else {
+                sbase[i] = nullptr;
+            }
+        }
+    };
+    auto issue_one = [&](auto tag, int kt, int stage, int i) {
+        typedef Cls<decltype(tag)::value> C;
+        unsigned char* sa = smem + stage * C::STAGE + wave_bytes;
+        unsigned char* sb = sa + C::A_BYTES;
+        if (i < C::CA) {
+            if (C::BMc >= 128 || wave < 4)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
+                                                 (__attribute__((address_space(3))) void*)(sa + i * 128 * ROW_BYTES), 16, 0, 0);
+        } else if (!FP8) {
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(bbase[i - C::CA] + (size_t)kt * BK * ESZ + b_voff),
+                (__attribute__((address_space(3))) void*)(sb + (i - C::CA) * 128 * ROW_BYTES), 16, 0, 0);
+        }
+    };
+    auto issue_slab = [&](auto tag, int kt, int stage) {
+        typedef Cls<decltype(tag)::value> C;
+#pragma unroll
+        for (int i = 0; i < C::CA + C::CB; ++i) issue_one(tag, kt, stage, i);
+    };
+    auto load_b_regs = [&](auto tag, int kt) {
+        typedef Cls<decltype(tag)::value> C;
+#pragma unroll
+        for (int i = 0; i < C::CB; ++i) {
+            rb[i] = *reinterpret_cast<const u32x2*>(bbase[i] + (size_t)kt * BK + b_voff);
+            rscale[i] = sbase[i][(kt * BK) >> 7];
+        }
+    };
+    auto store_b_regs = [&](auto tag, int stage) {
+        typedef Cls<decltype(tag)::value> C;
+        unsigned char* sb = smem + stage * C::STAGE + C::A_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * 128 * ROW_BYTES) = dequant8(rb[i], rscale[i]);
+    };
+    auto prologue = [&](auto tag) {
+        typedef Cls<decltype(tag)::value> C;
+        if (FP8) { load_b_regs(tag, 0); store_b_regs(tag, 0); if (KT > 1) load_b_regs(tag, 1); }
+#pragma unroll
+        for (int j = 0; j < C::NST; ++j)
+            if (j < KT) issue_slab(tag, j, j);
+    };
+    auto start_tile = [&](int blk, int nt_, int cls) {
+        if (cls == 0)      { setup(std::integral_constant<int, 4>{}, blk, nt_); prologue(std::integral_constant<int, 4>{}); }
+        else if (cls == 1) { setup(std::integral_constant<int, 2>{}, blk, nt_); prologue(std::integral_constant<int, 2>{}); }
+        else               { setup(std::integral_constant<int, 1>{}, blk, nt_); prologue(std::integral_constant<int, 1>{}); }
+    };
+
+    // One tile of the class given by `tag`; its first slabs are in flight.  Returns the class of the next tile
+    // (whose first slabs it has issued before its own epilogue) or -1.
+    auto run_tile = [&](auto tag) -> int {
+        typedef Cls<decltype(tag)::value> C;
+        constexpr int NST = C::NST;
+        constexpr int LPS = (C::BMc >= 128 ? C::CA : 0) + (FP8 ? 0 : C::CB);   // copies every wavefront issues per slab
+        const int wm = wave / C::WNW, wn = wave % C::WNW;
+        int brow[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            brow[q] = PHASE == 1 ? ((wn >> 1) * 256 + (q >> 1) * 128 + (wn & 1) * 64 + (q & 1) * 32) : (wn * 128 + q * 32);
+        auto load_frag_one = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks, int i) {
+            const unsigned char* sa = smem + stage * C::STAGE + (wm * 64) * ROW_BYTES;
+            const unsigned char* sb = smem + stage * C::STAGE + C::A_BYTES;
+            if (i < 4) wf[i] = *reinterpret_cast<const bf16x8*>(sb + brow[i] * ROW_BYTES + frag_off[ks]);
+            else       xf[i - 4] = *reinterpret_cast<const bf16x8*>(sa + (i - 4) * 32 * ROW_BYTES + frag_off[ks]);
+        };
+        auto load_frags = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks) {
+#pragma unroll
+            for (int i = 0; i < 4 + MB; ++i) load_frag_one(wf, xf, stage, ks, i);
+        };
+        auto wait_slabs = [&](int y) {
+            if (y >= 3) wait_vmcnt<3 * LPS>(); else if (y == 2) wait_vmcnt<2 * LPS>();
+            else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
+        };
+
+        f32x16 acc[MB][4];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
+
+        wait_slabs(min(NST - 1, KT - 1));
+        lds_barrier();                   // slab 0 is in LDS; everybody has read this tile's ticket
+        if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));             // ticket of the next tile
+        bf16x8 wf[2][4], xf[2][MB];
+        load_frags(wf[0], xf[0], 0, 0);
+
+        auto slab = [&](int kt, auto issue_tag) {
+            constexpr bool ISSUE = decltype(issue_tag)::value;
+            const int stage = kt % NST;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                bool copies = false;
+                if (ks + 1 < KS) {
+                    load_frags(wf[nxt], xf[nxt], stage, ks + 1);
+                } else if (ISSUE) {
+                    if (FP8) store_b_regs(tag, (kt + 1) % NST);
+                    wait_vmcnt<(NST - 2) * LPS>();
+                    lds_barrier();
+                    if (FP8) load_b_regs(tag, kt + 2);
+                    constexpr int NF = 4 + MB, NC = C::CA + (FP8 ? 0 : C::CB);
+#pragma unroll
+                    for (int i = 0; i < (NF > NC ? NF : NC); ++i) {
+                        if (i < NF) load_frag_one(wf[nxt], xf[nxt], (kt + 1) % NST, 0, i);
+                        if (i < NC) issue_one(tag, kt + NST, stage, i);
+                    }
+                    copies = true;
+                } else if (kt + 1 < KT) {
+                    if (FP8) store_b_regs(tag, (kt + 1) % NST);
+                    wait_slabs(min(NST - 2, KT - 2 - kt));
+                    lds_barrier();
+                    load_frags(wf[nxt], xf[nxt], (kt + 1) % NST, 0);
+                    if (FP8 && kt + 2 < KT) load_b_regs(tag, kt + 2);
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[mb][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][q], xf[cur][mb], acc[mb][q], 0, 0, 0);
+                constexpr int NMF = 4 * MB, NFR = 4 + MB, NCP = C::CA + C::CB;
+                if (copies) {
+#pragma unroll
+                    for (int i = 0; i < (NCP > NMF ? NCP : NMF); ++i) {
+                        if (i < NMF) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                        if (i < NFR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+                        if (i < NCP) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // slab copy
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NMF; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (i < NFR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        {
+            int kt = 0;
+            for (; kt + NST < KT; ++kt) slab(kt, std::true_type{});
+            for (; kt < KT; ++kt) slab(kt, std::false_type{});
+        }
+        lds_barrier();                   // every fragment is in registers: all stages are free; next ticket visible
+        const int em0 = m0, em_end = m_end, ent = nt;
+        const int nblk = s_ticket[0], nnt = s_ticket[1], ncls = s_ticket[2];
+        if (nblk >= 0) start_tile(nblk, nnt, ncls);                     // the next tile's first slabs fly during the epilogue
+
+        // ---- epilogue.  acc[mb][q][v]: row l31 of row block mb; column 8*(v>>2) + 4*lhi + (v&3) of column block q
+        const int ug = ent * C::U + (wn >> 1);
+        if (ug < NU) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int m = em0 + wm * 64 + mb * 32 + l31;
+                if (m < em_end) {
+                    if (PHASE == 1) {
+                        __bf16* out = a.h + (long long)m * a.f + ug * 128 + (wn & 1) * 64 + 4 * lhi;
+#pragma unroll
+                        for (int q = 0; q < 2; ++q)
+#pragma unroll
+                            for (int vg = 0; vg < 4; ++vg) {
+                                float hv[4];
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) hv[j] = silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j];
+                                *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
+                            }
+                    } else {
+                        __bf16* out = a.y + (long long)m * a.d + ug * 256 + (wn & 1) * 128 + 4 * lhi;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int vg = 0; vg < 4; ++vg)
+                                *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
+                                    pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        return nblk >= 0 ? ncls : -1;
+    };
+
+    int cls = s_ticket[2];
+    start_tile(s_ticket[0], s_ticket[1], cls);
+    while (cls >= 0) {
+        if (cls == 0)      cls = run_tile(std::integral_constant<int, 4>{});
+        else if (cls == 1) cls = run_tile(std::integral_constant<int, 2>{});
+        else               cls = run_tile(std::integral_constant<int, 1>{});
+    }
+}
+
 int plan_capacity(int M) { return M / 64 + MAX_GROUPS + 1; }
 size_t h_bytes(int M, int f) { return (((size_t)M * f * 2) + 255) & ~(size_t)255; }
 
@@ -492,6 +787,29 @@ moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     moe::LaunchScope k(PHASE == 1 ? "ffn_gemm1_kernel" : "ffn_gemm2_kernel", s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(S::WMW * 128), lds, s, a);
     return k.done();
+}
+
+template <int PHASE, bool FP8>
+moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s) {
+    static bool attr_done = false;
+    auto kern = ffn_adaptive_kernel<PHASE, FP8>;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ADAPTIVE_LDS);
+        if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
+        attr_done = true;
+    }
+    const long long slots = num_cus();
+    const int grid = (int)(max_tiles < slots ? max_tiles : slots);
+    moe::LaunchScope k(PHASE == 1 ? "ffn_gemm1_kernel" : "ffn_gemm2_kernel", s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ADAPTIVE_LDS, s, a);
+    return k.done();
+}
+
+template <bool FP8>
+moe_status launch_both_adaptive(const FfnArgs& a, long long max_blocks, hipStream_t s) {
+    moe_status st = launch_adaptive<1, FP8>(a, max_blocks * (a.f / 128), s);
+    if (st != MOE_OK) return st;
+    return launch_adaptive<2, FP8>(a, max_blocks * (a.d / 256), s);
 }
 
 template <int ROWS, bool FP8>
@@ -551,6 +869,8 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
         if (st != MOE_OK) return st;
     }
     const long long max_blocks = M / bm + G;
+    const char* fixed = getenv("MOE_FFN_FIXED_SHAPE");
+    if (bm == 256 && !fp8 && !(fixed && fixed[0] == '1')) return launch_both_adaptive<false>(a, max_blocks, s);
     if (fp8) {
         if (bm == 256) return launch_both<256, true>(a, max_blocks, s);
         if (bm == 128) return launch_both<128, true>(a, max_blocks, s);
