@@ -30,6 +30,8 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["tiny", "c2", "c3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy (reference reading for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -103,6 +105,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.ones((256 << 20,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                           # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- timed region
     moe.moe_kernel_timing_enable(True)
@@ -125,8 +133,8 @@ def main():
     flops_g1 = 4.0 * cfg.d * cfg.f * M                           # gate and up projections
     achieved = flops_g1 / (g1 * 1e-6) / 1e12
     roofline = {"kernel": "ffn_gemm1_kernel", "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "avg_launch_us": g1}
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": stored_traffic(args.workload),
+                "avg_launch_us": g1, "flop_per_launch": flops_g1}
     n_match = int(g_out["counts"][0].item())
     n_bvn = int(b_out["counts"][0].item())
     decomp_us = kernels["greedy_kernel"]["avg_us"]
@@ -154,6 +162,22 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r, x_h, W, M)
     print(json.dumps(result))
+
+
+def stored_traffic(workload):
+    """HBM-side bytes per launch of the dominant kernel from the committed counter summary (two rocprofv3 --pmc runs,
+    scaled by a plain copy of known size); None if that summary was taken on another workload or if the kernel's
+    source has changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic.json" % workload)
+    try:
+        rec = json.load(open(path))
+        for rel, digest in rec["source_sha256"].items():
+            if hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest() != digest:
+                return None
+        return rec["traffic_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def extras(moe, torch, np, workloads, dev):
@@ -222,15 +246,15 @@ def cpu_baseline(cfg, ids_h, r, x_h, W, M):
     t0 = time.perf_counter()
     offsets, _ = oracle.slice_table(ids_h, cfg.E, r, traffic, perms, dur, cfg.kmax, want_rows=False)
     t_slice = time.perf_counter() - t0
-    sample = min(M, 4096)
+    sample = M                                                   # the whole workload: a few seconds of CPU time
     rows = np.arange(sample)
     t0 = time.perf_counter()
     oracle.expert_ffn_sliced(x_h, offsets, cfg.E_loc, W, rows=rows)
     t_ffn = time.perf_counter() - t0
     tflops = 6.0 * cfg.d * cfg.f * sample / t_ffn / 1e12
     return {"value": tflops, "unit": "TFLOP/s", "cores": int(blas_threads), "kind": "oracle",
-            "sample": "FFN: first %d of %d rows in float64 numpy (%.2f s); histogram %.1f ms, greedy %.2f ms, BvN %.1f ms, "
-                      "slice table %.1f ms on the full workload, one thread each"
+            "sample": "FFN: %d of %d rows in float64 numpy (%.2f s, BLAS threads = cores); histogram %.1f ms, greedy %.2f ms, "
+                      "BvN %.1f ms, slice table %.1f ms on the full workload, one thread each"
                       % (sample, M, t_ffn, t_hist * 1e3, t_greedy * 1e3, t_bvn * 1e3, t_slice * 1e3),
             "decompositions_per_s": {"greedy": 1.0 / t_greedy, "bvn": 1.0 / t_bvn}}
 
