@@ -495,7 +495,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
     // slab layout and swizzle as in ffn_gemm_kernel (64-byte rows): chunk id = tid + i*512 -> row = tid/4 + 128*i
     const int row0 = tid >> 2;
     const int kcg = (tid & 3) ^ ((row0 >> 2) & 3);
-    const int wave_bytes = wave * 1024;
+    const int wave_bytes = __builtin_amdgcn_readfirstlane(wave) * 1024;       // scalar: LDS targets of the copies need no VALU
     const int st_off = row0 * ROW_BYTES + ((tid & 3) << 4);
     const int fswz = (l31 >> 2) & 3;
     int frag_off[KS];
@@ -504,7 +504,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
 
     // thread 0 pulls tickets (own queue first, then the others).  A ticket names (block, unit); it is a tile only if
     // the unit is the first of the tile its block's class makes of it.
-    auto fetch = [&](int first_k) {
+    auto fetch = [&](int first_k) __attribute__((always_inline)) {
         int q = my_xcd, k = first_k, blk = -1, unit = -1, cls = 0;
         for (int tries = 0; tries < 8;) {
             int st = geom.decode(q, k, blk, unit);
@@ -522,60 +522,75 @@ void ffn_adaptive_kernel(FfnArgs a) {
     __syncthreads();
     if (s_ticket[0] < 0) return;
 
-    // ---- per-tile copy state
+    // ---- per-tile copy state.  Slab copies are buffer loads with an LDS destination: the resource and the scalar
+    //      offset carry everything that is uniform (expert, column unit, K position), the per-thread byte offset is
+    //      fixed for a tile, so a copy costs no vector ALU work.
     const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)Abase, 0, 0xFFFFFFFF, 0x00020000);
+    __amdgpu_buffer_rsrc_t rsB0 = rsA, rsB1 = rsA;                  // phase 1: gate / up of the tile's expert; phase 2: down
     const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
     int m0 = 0, m_end = 0, nt = 0;
-    int a_off[2];
-    const unsigned char* bbase[8];
+    unsigned int a_voff[2];
+    unsigned int b_soff[8];
+    const unsigned char* bbase[8];                                 // fp8 only: codes go through registers
     const float* sbase[8];
     u32x2 rb[8];
     float rscale[8];
 
-    auto setup = [&](auto tag, int blk, int nt_) {
+    auto setup = [&](auto tag, int blk_, int nt_) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
+        const int blk = __builtin_amdgcn_readfirstlane(blk_);
+        nt = __builtin_amdgcn_readfirstlane(nt_);
         const int4 info = a.plan[PLAN_HDR + blk];
-        m0 = info.x; m_end = info.y; nt = nt_;
+        m0 = info.x; m_end = info.y;
         const int e = info.z;
         const int rows = min(C::BMc, m_end - m0);
 #pragma unroll
-        for (int i = 0; i < C::CA; ++i) a_off[i] = (m0 + min(row0 + 128 * i, rows - 1)) * K + kcg * 8;
+        for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)((m0 + min(row0 + 128 * i, rows - 1)) * K + kcg * 8) * 2u;
+        if (PHASE == 1) {
+            rsB0 = __builtin_amdgcn_make_buffer_rsrc((void*)((const unsigned char*)a.wg + (size_t)e * a.f * K * ESZ), 0, 0xFFFFFFFF, 0x00020000);
+            rsB1 = __builtin_amdgcn_make_buffer_rsrc((void*)((const unsigned char*)a.wu + (size_t)e * a.f * K * ESZ), 0, 0xFFFFFFFF, 0x00020000);
+        } else {
+            rsB0 = __builtin_amdgcn_make_buffer_rsrc((void*)((const unsigned char*)a.wd + (size_t)e * a.d * K * ESZ), 0, 0xFFFFFFFF, 0x00020000);
+            rsB1 = rsB0;
+        }
 #pragma unroll
         for (int i = 0; i < C::CB; ++i) {                                 // 128-row strips of the B slab
             const int ug = min(nt * C::U + (i >> 1), NU - 1);
-            long long wrow;
-            const void* w;
-            if (PHASE == 1) { wrow = (long long)e * a.f + ug * 128;               w = (i & 1) ? a.wu : a.wg; }
-            else            { wrow = (long long)e * a.d + ug * 256 + (i & 1) * 128; w = a.wd; }
-            bbase[i] = (const unsigned char*)w + wrow * K * ESZ;
+            const int strip_row = PHASE == 1 ? ug * 128 : ug * 256 + (i & 1) * 128;     // row inside the expert's matrix
+            b_soff[i] = (unsigned int)strip_row * (unsigned int)K * ESZ;
             if (FP8) {
+                const void* w = PHASE == 1 ? ((i & 1) ? a.wu : a.wg) : a.wd;
+                const long long wrow = (long long)e * (PHASE == 1 ? a.f : a.d) + strip_row;
+                bbase[i] = (const unsigned char*)w + wrow * K;
                 if (PHASE == 1) sbase[i] = ((i & 1) ? a.su : a.sg) + ((long long)e * (a.f / 128) + ug) * (K / 128);
                 else            sbase[i] = a.sd + ((long long)e * (a.d / 128) + ug * 2 + (i & 1)) * (K / 128);
             } else {
-                sbase[i] = nullptr;
+                bbase[i] = nullptr; sbase[i] = nullptr;
             }
         }
     };
-    auto issue_one = [&](auto tag, int kt, int stage, int i) {
+    auto issue_one = [&](auto tag, int kt, int stage, int i) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
         unsigned char* sa = smem + stage * C::STAGE + wave_bytes;
         unsigned char* sb = sa + C::A_BYTES;
         if (i < C::CA) {
             if (C::BMc >= 128 || wave < 4)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Abase + a_off[i] + kt * BK),
-                                                 (__attribute__((address_space(3))) void*)(sa + i * 128 * ROW_BYTES), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(sa + i * 128 * ROW_BYTES), 16,
+                                                         a_voff[i], kt * (BK * 2), 0, 0);
         } else if (!FP8) {
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(bbase[i - C::CA] + (size_t)kt * BK * ESZ + b_voff),
-                (__attribute__((address_space(3))) void*)(sb + (i - C::CA) * 128 * ROW_BYTES), 16, 0, 0);
+            const int j = i - C::CA;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds((j & 1) ? rsB1 : rsB0,
+                                                     (__attribute__((address_space(3))) void*)(sb + j * 128 * ROW_BYTES), 16, b_voff,
+                                                     b_soff[j] + kt * (BK * ESZ), 0, 0);
         }
     };
-    auto issue_slab = [&](auto tag, int kt, int stage) {
+    auto issue_slab = [&](auto tag, int kt, int stage) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
 #pragma unroll
         for (int i = 0; i < C::CA + C::CB; ++i) issue_one(tag, kt, stage, i);
     };
-    auto load_b_regs = [&](auto tag, int kt) {
+    auto load_b_regs = [&](auto tag, int kt) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
 #pragma unroll
         for (int i = 0; i < C::CB; ++i) {
@@ -583,20 +598,20 @@ void ffn_adaptive_kernel(FfnArgs a) {
             rscale[i] = sbase[i][(kt * BK) >> 7];
         }
     };
-    auto store_b_regs = [&](auto tag, int stage) {
+    auto store_b_regs = [&](auto tag, int stage) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
         unsigned char* sb = smem + stage * C::STAGE + C::A_BYTES;
 #pragma unroll
         for (int i = 0; i < C::CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * 128 * ROW_BYTES) = dequant8(rb[i], rscale[i]);
     };
-    auto prologue = [&](auto tag) {
+    auto prologue = [&](auto tag) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
         if (FP8) { load_b_regs(tag, 0); store_b_regs(tag, 0); if (KT > 1) load_b_regs(tag, 1); }
 #pragma unroll
         for (int j = 0; j < C::NST; ++j)
             if (j < KT) issue_slab(tag, j, j);
     };
-    auto start_tile = [&](int blk, int nt_, int cls) {
+    auto start_tile = [&](int blk, int nt_, int cls) __attribute__((always_inline)) {
         if (cls == 0)      { setup(std::integral_constant<int, 4>{}, blk, nt_); prologue(std::integral_constant<int, 4>{}); }
         else if (cls == 1) { setup(std::integral_constant<int, 2>{}, blk, nt_); prologue(std::integral_constant<int, 2>{}); }
         else               { setup(std::integral_constant<int, 1>{}, blk, nt_); prologue(std::integral_constant<int, 1>{}); }
@@ -604,7 +619,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
 
     // One tile of the class given by `tag`; its first slabs are in flight.  Returns the class of the next tile
     // (whose first slabs it has issued before its own epilogue) or -1.
-    auto run_tile = [&](auto tag) -> int {
+    auto run_tile = [&](auto tag) __attribute__((always_inline)) -> int {
         typedef Cls<decltype(tag)::value> C;
         constexpr int NST = C::NST;
         constexpr int LPS = (C::BMc >= 128 ? C::CA : 0) + (FP8 ? 0 : C::CB);   // copies every wavefront issues per slab
@@ -623,7 +638,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
 #pragma unroll
             for (int i = 0; i < 4 + MB; ++i) load_frag_one(wf, xf, stage, ks, i);
         };
-        auto wait_slabs = [&](int y) {
+        auto wait_slabs = [&](int y) __attribute__((always_inline)) {
             if (y >= 3) wait_vmcnt<3 * LPS>(); else if (y == 2) wait_vmcnt<2 * LPS>();
             else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
         };
@@ -642,7 +657,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
         bf16x8 wf[2][4], xf[2][MB];
         load_frags(wf[0], xf[0], 0, 0);
 
-        auto slab = [&](int kt, auto issue_tag) {
+        auto slab = [&](int kt, auto issue_tag) __attribute__((always_inline)) {
             constexpr bool ISSUE = decltype(issue_tag)::value;
             const int stage = kt % NST;
 #pragma unroll
