@@ -159,6 +159,7 @@ def main():
     # ---------------------------------------------------------------- extras outside the timed step
     if not args.no_extras:
         result["extras"] = extras(moe, torch, np, workloads, dev)
+        result["extras"].update(ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ffn_ws))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r, x_h, W, M)
     print(json.dumps(result))
@@ -221,6 +222,48 @@ def extras(moe, torch, np, workloads, dev):
     dt = (time.perf_counter() - t0) / reps
     nbytes = ids.numel() * 4 + tr.numel() * 4 + cn.numel() * 4
     out["histogram_64_layers"] = {"bytes": nbytes, "GB_per_s": nbytes / dt / 1e9, "frac_hbm_peak": nbytes / dt / 1e9 / HBM_PEAK_GBS}
+    return out
+
+
+def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ffn_ws):
+    """(i) the same schedule issued as one call per slice (what per-matching launches would cost) beside the single
+    call; (ii) expert time against the number of rows of a single slice -- this GPU's version of the paper's Figure 1."""
+    out = {}
+    dev = x.device
+    off_h = offsets.cpu().numpy().astype(np.int64)
+    reps = 20
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e6
+
+    one_call = timed(lambda: moe.moe_expert_ffn_sliced(x, offsets, S, E_loc, wg, wu, wd, y=y, workspace=ffn_ws))
+    per_slice = []
+    for sl in range(S):
+        lo, hi = int(off_h[sl * E_loc]), int(off_h[(sl + 1) * E_loc])
+        if hi > lo:
+            o = torch.from_numpy((off_h[sl * E_loc:(sl + 1) * E_loc + 1] - lo).astype(np.int32)).to(dev)
+            per_slice.append((x[lo:hi], o, y[lo:hi]))
+
+    def run_slices():
+        for xs, o, ys in per_slice:
+            moe.moe_expert_ffn_sliced(xs, o, 1, E_loc, wg, wu, wd, y=ys, workspace=ffn_ws)
+
+    out["ffn_one_call_us"] = one_call
+    out["ffn_one_call_per_slice_us"] = timed(run_slices)
+    out["ffn_slices"] = len(per_slice)
+    curve = {}
+    for rows in (1, 8, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
+        if rows > x.shape[0]:
+            break
+        o = torch.tensor([0, rows] + [rows] * (E_loc - 1), dtype=torch.int32, device=dev)      # all rows on local expert 0
+        curve[str(rows)] = timed(lambda: moe.moe_expert_ffn_sliced(x[:rows], o, 1, E_loc, wg, wu, wd, y=y[:rows], workspace=ffn_ws))
+    out["expert_time_us_vs_rows"] = curve
     return out
 
 

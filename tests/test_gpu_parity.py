@@ -345,3 +345,20 @@ def test_whole_path_c4_fp8(lib):
     r = int(order[len(order) // 2])
     res = run_path(lib, cfg, r, "greedy")
     check_path(cfg, r, res, "greedy", n_sample=128)
+
+
+def test_decompose_stress_batch_hashes(lib):
+    """A larger slice of the batched stress workload in count/hash-only mode: every schedule hash equals the
+    oracle's, and the full batch size runs with sane counts."""
+    say("decompose stress batch hashes")
+    mats = workloads.stress_matrices(1024, 128)
+    out = lib.moe_decompose_greedy(dev(mats), 32, zero_diag=True, want_perms=False, want_residual=False, want_hashes=True)
+    torch.cuda.synchronize()
+    ref = oracle.decompose_batch("greedy", mats, 32, zero_diag=True, nthreads=16, want_perms=False, want_residual=False)
+    assert np.array_equal(out["counts"].cpu().numpy(), ref["counts"])
+    assert np.array_equal(out["hashes"].cpu().numpy().view(np.uint64), ref["hashes"])
+    assert np.array_equal(out["durations"].cpu().numpy(), ref["durations"])
+    big = torch.from_numpy(np.tile(mats, (8, 1, 1))).to(DEV)                 # 8192 matrices, the stress batch size
+    out8 = lib.moe_decompose_greedy(big, 32, zero_diag=True, want_perms=False, want_residual=False, want_hashes=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(out8["hashes"].cpu().numpy().view(np.uint64), np.tile(ref["hashes"], 8))
