@@ -6,11 +6,12 @@
 // Two grouped GEMMs on the bf16 MFMA units, each a persistent kernel looping over output tiles:
 //   phase 1:  H = silu(X Wg^T) * (X Wu^T)     tile = BM rows x (128 gate + 128 up) columns
 //   phase 2:  Y = H Wd^T                      tile = BM rows x 256 columns
-// A tile never spans two (slice, expert) groups.  Both operands are K-contiguous, are staged
-// global -> registers -> LDS in 64-wide K slabs (double buffered, XOR-swizzled 16-byte chunks)
-// and read back as 16-byte MFMA fragments.  4 wavefronts = 2 (rows) x 2 (columns); the weights
-// feed the MFMA "A" port so that each lane ends up with 4 consecutive output columns of one row
-// and can store 8 bytes at a time.
+// A tile never spans two (slice, expert) groups.  Both operands are K-contiguous, are copied
+// global -> LDS in K slabs (2 to 4 in flight, XOR-swizzled 16-byte chunks; fp8 weights pass through
+// registers to be dequantised) and read back as 16-byte MFMA fragments.  The weights feed the MFMA
+// "A" port so that each lane ends up with 4 consecutive output columns of one row and can store
+// 8 bytes at a time.  bf16 schedules with large groups run ffn_adaptive_kernel, the others (and
+// fp8 weights) the fixed-shape ffn_gemm_kernel.
 #include "common.hpp"
 #include <stdlib.h>
 #include <type_traits>
@@ -455,52 +456,68 @@ void ffn_gemm_kernel(FfnArgs a) {
     }
 }
 
-// ---------------------------------------------------------------------------------- adaptive-shape GEMM kernel
-// Same pipeline as above with 8 wavefronts of 64 x 128 each, but the arrangement of the wavefronts is chosen per
-// row block so that ragged slices do not pay for 256 rows they do not have:
-//   class 0: 4 x 2 wavefronts = 256 rows x 256 columns   (4 stages of 32 KiB)
-//   class 1: 2 x 4            = 128 rows x 512 columns   (3 stages of 40 KiB)
-//   class 2: 1 x 8            =  64 rows x 1024 columns  (2 stages of 68 KiB)
+// ---------------------------------------------------------------------------------- adaptive-shape GEMM kernel (bf16)
+// Same dataflow as ffn_gemm_kernel with 8 wavefronts of 64 x 128 each, but the arrangement of the wavefronts is chosen
+// per row block so that ragged slices do not pay for 256 rows they do not have:
+//   class 0: 4 x 2 wavefronts = 256 rows x 256 columns;  64-wide K slabs (128-byte rows) of 64 KiB, two in LDS
+//   class 1: 2 x 4            = 128 rows x 512 columns;  32-wide K slabs (64-byte rows) of 40 KiB, three in LDS
+//   class 2: 1 x 8            =  64 rows x 1024 columns; 32-wide K slabs of 68 KiB, two in LDS
 // Every class runs the same number of MFMAs per tile; a block of <= 64 rows needs a quarter of the tiles of class 0.
 // Columns come in units (phase 1: 128 hidden units = 128 gate + 128 up rows; phase 2: 256 rows of w_down); a tile of
 // class c covers 1 / 2 / 4 consecutive units.  A unit past the end is fetched as the last valid one and not stored.
-template <int WMW> struct Cls {
-    static constexpr int WNW = 8 / WMW, U = WNW / 2;
-    static constexpr int BMc = 64 * WMW, BNc = 128 * WNW;
-    static constexpr int A_BYTES = BMc * 64, B_BYTES = BNc * 64, STAGE = A_BYTES + B_BYTES;
-    static constexpr int NST = WMW == 4 ? 4 : (WMW == 2 ? 3 : 2);
-    static constexpr int CA = WMW >= 2 ? WMW / 2 : 1;          // WMW == 1: only the first 4 wavefronts copy A rows
-    static constexpr int CB = WNW;
-    static constexpr int ID = WMW == 4 ? 0 : (WMW == 2 ? 1 : 2);
+// The 256-row class, which does most of the work, has 128-byte slab rows so that every copy fetches whole cache
+// lines: a 64-byte row is half a line whose other half is requested again by the next slab, which doubles the
+// requests to the L2 and the fill traffic into the L1 and keeps the address FIFO of the memory pipeline full (and
+// the MFMAs queued behind a copy waiting) for a fifth of the time.
+// The barrier at the end of slab s publishes slab s + 1 and frees the buffer of slab s; the copies of slab s + NSS
+// go out from there on, spaced between the MFMAs (slot 0 = rest of slab s, slot i = K step i - 1 of slab s + 1).
+template <int CLS> struct Cls {
+    static constexpr int WMW = CLS == 0 ? 4 : (CLS == 1 ? 2 : 1), WNW = 8 / WMW;
+    static constexpr int MB = 2, NQ = 4;                                    // 32-row / 32-column blocks per wavefront
+    static constexpr int BMc = 32 * MB * WMW, BNc = 32 * NQ * WNW;
+    static constexpr int U = BNc / 256;                                     // column units per tile
+    static constexpr int ROWB = CLS == 0 ? 128 : 64;                        // bytes per slab row
+    static constexpr int SUB = ROWB / 32;                                   // MFMA K steps (of 16) per slab
+    static constexpr int RPC = 8192 / ROWB;                                 // slab rows one copy of the workgroup deposits
+    static constexpr int A_BYTES = BMc * ROWB, B_BYTES = BNc * ROWB, SLAB = A_BYTES + B_BYTES;
+    static constexpr int NSS = CLS == 1 ? 3 : 2;                            // slabs resident in LDS
+    static constexpr int CA = BMc >= RPC ? BMc / RPC : 1;                   // class 2: only wavefronts 0..3 copy the 64 A rows
+    static constexpr int CB = BNc / RPC, NCOPY = CA + CB;                   // copies per wavefront and slab
+    static constexpr bool A_HALF = BMc < RPC;
+    // copies per slot (slot 0, 1, 2; none later)
+    static constexpr int S0 = CLS == 0 ? 4 : (CLS == 1 ? 3 : NCOPY), S1 = CLS == 0 ? 4 : (CLS == 1 ? 2 : 0), S2 = 0;
+    static_assert(S0 + S1 + S2 == NCOPY && (S2 == 0 || SUB > 2) && (S1 == 0 || SUB > 1), "the slots hold every copy and end before the next slab's last K step");
 };
-constexpr int ADAPTIVE_LDS = 2 * Cls<1>::STAGE;                // 136 KiB >= 4 * 32 KiB, 3 * 40 KiB
+constexpr int ADAPTIVE_LDS = 139264;                          // 2 x 68 KiB (class 2) >= 2 x 64 KiB, 3 x 40 KiB
 
-template <int PHASE, bool FP8>
+template <int PHASE>
 __global__ __launch_bounds__(512, 1)
 void ffn_adaptive_kernel(FfnArgs a) {
-    constexpr int BK = 32, ROW_BYTES = 64, KS = 2, MB = 2, ESZ = FP8 ? 1 : 2;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int s_ticket[3];                        // (block, tile index, class) of the next tile; block -1 = none
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, lhi = lane >> 5;
     const int K = PHASE == 1 ? a.d : a.f;
-    const int KT = K / BK;
     const int NU = PHASE == 1 ? a.f / 128 : a.d / 256;          // column units
     TileGeom geom;
     geom.init(a.plan[0].x, NU);
     int* queues = (int*)(a.plan + (PHASE == 1 ? 1 : 3));
     const int my_xcd = blockIdx.x & 7;
 
-    // slab layout and swizzle as in ffn_gemm_kernel (64-byte rows): chunk id = tid + i*512 -> row = tid/4 + 128*i
-    const int row0 = tid >> 2;
-    const int kcg = (tid & 3) ^ ((row0 >> 2) & 3);
-    const int wave_bytes = __builtin_amdgcn_readfirstlane(wave) * 1024;       // scalar: LDS targets of the copies need no VALU
-    const int st_off = row0 * ROW_BYTES + ((tid & 3) << 4);
-    const int fswz = (l31 >> 2) & 3;
-    int frag_off[KS];
+    // Slab layout: row-major, 16-byte chunk c of row r sits at position c ^ swz(r); swz(r) = (r >> 2) & 3 for 64-byte
+    // rows and (r >> 1) & 7 for 128-byte rows (16 consecutive rows of a fragment read then cover all 64 banks).
+    // One copy instruction of the workgroup deposits 8 KiB = RPC whole rows: thread t writes position t % (ROWB / 16)
+    // of row t / (ROWB / 16), so it fetches the chunk that belongs there.
+    const int row0_64 = tid >> 2, row0_128 = tid >> 3;
+    const int kcg_64 = (tid & 3) ^ ((row0_64 >> 2) & 3), kcg_128 = (tid & 7) ^ ((row0_128 >> 1) & 7);
+    const int wave_bytes = wave * 1024;
+    int frag_off64[2], frag_off128[4];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) frag_off[ks] = l31 * ROW_BYTES + ((((ks << 1) | lhi) ^ fswz) << 4);
+    for (int u = 0; u < 2; ++u) frag_off64[u] = l31 * 64 + ((((u << 1) | lhi) ^ ((l31 >> 2) & 3)) << 4);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) frag_off128[u] = l31 * 128 + ((((u << 1) | lhi) ^ ((l31 >> 1) & 7)) << 4);
 
     // thread 0 pulls tickets (own queue first, then the others).  A ticket names (block, unit); it is a tile only if
     // the unit is the first of the tile its block's class makes of it.
@@ -522,200 +539,183 @@ void ffn_adaptive_kernel(FfnArgs a) {
     __syncthreads();
     if (s_ticket[0] < 0) return;
 
-    // ---- per-tile copy state.  Slab copies are buffer loads with an LDS destination: the resource and the scalar
-    //      offset carry everything that is uniform (expert, column unit, K position), the per-thread byte offset is
-    //      fixed for a tile, so a copy costs no vector ALU work.
+    // ---- per-tile copy state: buffer resources and scalar offsets carry what is uniform, the per-thread byte offsets
+    //      are fixed for a tile, so a copy costs no vector ALU work.  Rows past the end of the block re-read its last row.
     const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)Abase, 0, 0xFFFFFFFF, 0x00020000);
-    __amdgpu_buffer_rsrc_t rsB0 = rsA, rsB1 = rsA;                  // phase 1: gate / up of the tile's expert; phase 2: down
-    const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
+    // B rows come from w_gate / w_up (phase 1) or w_down (phase 2) of the tile's expert: base address of the first and
+    // distance to the second.  (One variable per quantity, set once per tile: a choice between variables inside the
+    // unrolled copy code would keep them in memory.)
+    unsigned long long wB = 0, wB_up = 0;
+    unsigned int b_voff = 0;
     int m0 = 0, m_end = 0, nt = 0;
-    unsigned int a_voff[2];
+    unsigned int a_voff[4];
     unsigned int b_soff[8];
-    const unsigned char* bbase[8];                                 // fp8 only: codes go through registers
-    const float* sbase[8];
-    u32x2 rb[8];
-    float rscale[8];
 
     auto setup = [&](auto tag, int blk_, int nt_) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
         const int blk = __builtin_amdgcn_readfirstlane(blk_);
         nt = __builtin_amdgcn_readfirstlane(nt_);
         const int4 info = a.plan[PLAN_HDR + blk];
-        m0 = info.x; m_end = info.y;
-        const int e = info.z;
+        m0 = __builtin_amdgcn_readfirstlane(info.x); m_end = __builtin_amdgcn_readfirstlane(info.y);
+        const int e = __builtin_amdgcn_readfirstlane(info.z);
         const int rows = min(C::BMc, m_end - m0);
+        const int row0 = C::ROWB == 128 ? row0_128 : row0_64, kcg = C::ROWB == 128 ? kcg_128 : kcg_64;
 #pragma unroll
-        for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)((m0 + min(row0 + 128 * i, rows - 1)) * K + kcg * 8) * 2u;
+        for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)((m0 + min(row0 + C::RPC * i, rows - 1)) * K + kcg * 8) * 2u;
         if (PHASE == 1) {
-            rsB0 = __builtin_amdgcn_make_buffer_rsrc((void*)((const unsigned char*)a.wg + (size_t)e * a.f * K * ESZ), 0, 0xFFFFFFFF, 0x00020000);
-            rsB1 = __builtin_amdgcn_make_buffer_rsrc((void*)((const unsigned char*)a.wu + (size_t)e * a.f * K * ESZ), 0, 0xFFFFFFFF, 0x00020000);
+            wB = (unsigned long long)((const __bf16*)a.wg + (size_t)e * a.f * K);
+            wB_up = (unsigned long long)((const __bf16*)a.wu + (size_t)e * a.f * K) - wB;
         } else {
-            rsB0 = __builtin_amdgcn_make_buffer_rsrc((void*)((const unsigned char*)a.wd + (size_t)e * a.d * K * ESZ), 0, 0xFFFFFFFF, 0x00020000);
-            rsB1 = rsB0;
+            wB = (unsigned long long)((const __bf16*)a.wd + (size_t)e * a.d * K);
+            wB_up = 0;
         }
+        b_voff = (unsigned int)(row0 * K + kcg * 8) * 2u;
+        constexpr int CPSTRIP = 128 / C::RPC;                             // copies per 128-row strip of the B slab
 #pragma unroll
-        for (int i = 0; i < C::CB; ++i) {                                 // 128-row strips of the B slab
-            const int ug = min(nt * C::U + (i >> 1), NU - 1);
-            const int strip_row = PHASE == 1 ? ug * 128 : ug * 256 + (i & 1) * 128;     // row inside the expert's matrix
-            b_soff[i] = (unsigned int)strip_row * (unsigned int)K * ESZ;
-            if (FP8) {
-                const void* w = PHASE == 1 ? ((i & 1) ? a.wu : a.wg) : a.wd;
-                const long long wrow = (long long)e * (PHASE == 1 ? a.f : a.d) + strip_row;
-                bbase[i] = (const unsigned char*)w + wrow * K;
-                if (PHASE == 1) sbase[i] = ((i & 1) ? a.su : a.sg) + ((long long)e * (a.f / 128) + ug) * (K / 128);
-                else            sbase[i] = a.sd + ((long long)e * (a.d / 128) + ug * 2 + (i & 1)) * (K / 128);
-            } else {
-                bbase[i] = nullptr; sbase[i] = nullptr;
+        for (int j = 0; j < C::CB; ++j) {
+            const int strip = j / CPSTRIP;
+            const int ug = min(nt * C::U + (strip >> 1), NU - 1);
+            const int strip_row = PHASE == 1 ? ug * 128 : ug * 256 + (strip & 1) * 128;   // row inside the expert's matrix
+            b_soff[j] = (unsigned int)(strip_row + (j % CPSTRIP) * C::RPC) * (unsigned int)K * 2u;
+        }
+    };
+    // copy n of slab s into slab buffer sbuf
+    auto issue_copy = [&](auto tag, int s, int sbuf, int n) __attribute__((always_inline)) {
+        typedef Cls<decltype(tag)::value> C;
+        constexpr int CPSTRIP = 128 / C::RPC;
+        unsigned char* base = smem + sbuf * C::SLAB + wave_bytes;
+        const int koff = s * C::ROWB;                           // (plain locals: the builtin's operands must not be dependent expressions)
+        if (n < C::CA) {
+            if (!C::A_HALF || wave < 4)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
+                                                         a_voff[n], koff, 0, 0);
+        } else {
+            const int j = n - C::CA;
+            const unsigned long long up = (j / CPSTRIP) & 1;
+            const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)(wB + up * wB_up), 0, 0xFFFFFFFF, 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB,
+                                                     (__attribute__((address_space(3))) void*)(base + C::A_BYTES + j * 8192), 16,
+                                                     b_voff, b_soff[j] + koff, 0, 0);
+        }
+    };
+    auto prologue = [&](auto tag, int K_) __attribute__((always_inline)) {
+        typedef Cls<decltype(tag)::value> C;
+        const int NS = K_ / (C::ROWB / 2);
+#pragma unroll
+        for (int s = 0; s < C::NSS; ++s)
+            if (s < NS) {
+#pragma unroll
+                for (int n = 0; n < C::NCOPY; ++n) issue_copy(tag, s, s, n);
             }
-        }
-    };
-    auto issue_one = [&](auto tag, int kt, int stage, int i) __attribute__((always_inline)) {
-        typedef Cls<decltype(tag)::value> C;
-        unsigned char* sa = smem + stage * C::STAGE + wave_bytes;
-        unsigned char* sb = sa + C::A_BYTES;
-        if (i < C::CA) {
-            if (C::BMc >= 128 || wave < 4)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(sa + i * 128 * ROW_BYTES), 16,
-                                                         a_voff[i], kt * (BK * 2), 0, 0);
-        } else if (!FP8) {
-            const int j = i - C::CA;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds((j & 1) ? rsB1 : rsB0,
-                                                     (__attribute__((address_space(3))) void*)(sb + j * 128 * ROW_BYTES), 16, b_voff,
-                                                     b_soff[j] + kt * (BK * ESZ), 0, 0);
-        }
-    };
-    auto issue_slab = [&](auto tag, int kt, int stage) __attribute__((always_inline)) {
-        typedef Cls<decltype(tag)::value> C;
-#pragma unroll
-        for (int i = 0; i < C::CA + C::CB; ++i) issue_one(tag, kt, stage, i);
-    };
-    auto load_b_regs = [&](auto tag, int kt) __attribute__((always_inline)) {
-        typedef Cls<decltype(tag)::value> C;
-#pragma unroll
-        for (int i = 0; i < C::CB; ++i) {
-            rb[i] = *reinterpret_cast<const u32x2*>(bbase[i] + (size_t)kt * BK + b_voff);
-            rscale[i] = sbase[i][(kt * BK) >> 7];
-        }
-    };
-    auto store_b_regs = [&](auto tag, int stage) __attribute__((always_inline)) {
-        typedef Cls<decltype(tag)::value> C;
-        unsigned char* sb = smem + stage * C::STAGE + C::A_BYTES;
-#pragma unroll
-        for (int i = 0; i < C::CB; ++i) *reinterpret_cast<u32x4*>(sb + st_off + i * 128 * ROW_BYTES) = dequant8(rb[i], rscale[i]);
-    };
-    auto prologue = [&](auto tag) __attribute__((always_inline)) {
-        typedef Cls<decltype(tag)::value> C;
-        if (FP8) { load_b_regs(tag, 0); store_b_regs(tag, 0); if (KT > 1) load_b_regs(tag, 1); }
-#pragma unroll
-        for (int j = 0; j < C::NST; ++j)
-            if (j < KT) issue_slab(tag, j, j);
     };
     auto start_tile = [&](int blk, int nt_, int cls) __attribute__((always_inline)) {
-        if (cls == 0)      { setup(std::integral_constant<int, 4>{}, blk, nt_); prologue(std::integral_constant<int, 4>{}); }
-        else if (cls == 1) { setup(std::integral_constant<int, 2>{}, blk, nt_); prologue(std::integral_constant<int, 2>{}); }
-        else               { setup(std::integral_constant<int, 1>{}, blk, nt_); prologue(std::integral_constant<int, 1>{}); }
+        if (cls == 0)      { setup(std::integral_constant<int, 0>{}, blk, nt_); prologue(std::integral_constant<int, 0>{}, K); }
+        else if (cls == 1) { setup(std::integral_constant<int, 1>{}, blk, nt_); prologue(std::integral_constant<int, 1>{}, K); }
+        else               { setup(std::integral_constant<int, 2>{}, blk, nt_); prologue(std::integral_constant<int, 2>{}, K); }
     };
 
-    // One tile of the class given by `tag`; its first slabs are in flight.  Returns the class of the next tile
+    // One tile of the class given by `tag`; its first NSS slabs are in flight.  Returns the class of the next tile
     // (whose first slabs it has issued before its own epilogue) or -1.
     auto run_tile = [&](auto tag) __attribute__((always_inline)) -> int {
         typedef Cls<decltype(tag)::value> C;
-        constexpr int NST = C::NST;
-        constexpr int LPS = (C::BMc >= 128 ? C::CA : 0) + (FP8 ? 0 : C::CB);   // copies every wavefront issues per slab
+        constexpr int MB = C::MB, NQ = C::NQ, NSS = C::NSS, SUB = C::SUB;
+        constexpr int ROWB = C::ROWB, NMF = MB * NQ, NR = MB + NQ;
+        constexpr int LPS = C::NCOPY - (C::A_HALF ? 1 : 0);             // copies every wavefront issues per slab
+        static_assert(NSS * C::NCOPY < 64 && NSS * C::SLAB <= ADAPTIVE_LDS, "pipeline shape");
+        const int NS = K / (ROWB / 2);
         const int wm = wave / C::WNW, wn = wave % C::WNW;
-        int brow[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            brow[q] = PHASE == 1 ? ((wn >> 1) * 256 + (q >> 1) * 128 + (wn & 1) * 64 + (q & 1) * 32) : (wn * 128 + q * 32);
-        auto load_frag_one = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks, int i) {
-            const unsigned char* sa = smem + stage * C::STAGE + (wm * 64) * ROW_BYTES;
-            const unsigned char* sb = smem + stage * C::STAGE + C::A_BYTES;
-            if (i < 4) wf[i] = *reinterpret_cast<const bf16x8*>(sb + brow[i] * ROW_BYTES + frag_off[ks]);
-            else       xf[i - 4] = *reinterpret_cast<const bf16x8*>(sa + (i - 4) * 32 * ROW_BYTES + frag_off[ks]);
-        };
-        auto load_frags = [&](bf16x8 (&wf)[4], bf16x8 (&xf)[MB], int stage, int ks) {
-#pragma unroll
-            for (int i = 0; i < 4 + MB; ++i) load_frag_one(wf, xf, stage, ks, i);
+        const int b_wave_row = PHASE == 1 ? (wn >> 1) * 256 + (wn & 1) * 64 : wn * 128;
+        auto bq = [](int q) { return PHASE == 1 ? (q >> 1) * 128 + (q & 1) * 32 : q * 32; };
+        const unsigned char* fragA = smem + (wm * 32 * MB) * ROWB;
+        const unsigned char* fragB = smem + C::A_BYTES + b_wave_row * ROWB;
+
+        auto load_frag_one = [&](bf16x8 (&wf)[NQ], bf16x8 (&xf)[MB], int sbuf, int u, int i) __attribute__((always_inline)) {
+            const int off = sbuf * C::SLAB + (ROWB == 128 ? frag_off128[u] : frag_off64[u & 1]);
+            if (i < NQ) wf[i] = *reinterpret_cast<const bf16x8*>(fragB + off + bq(i) * ROWB);
+            else        xf[i - NQ] = *reinterpret_cast<const bf16x8*>(fragA + off + (i - NQ) * 32 * ROWB);
         };
         auto wait_slabs = [&](int y) __attribute__((always_inline)) {
-            if (y >= 3) wait_vmcnt<3 * LPS>(); else if (y == 2) wait_vmcnt<2 * LPS>();
-            else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
+            if (y >= 2) wait_vmcnt<2 * LPS>(); else if (y == 1) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
         };
 
-        f32x16 acc[MB][4];
+        f32x16 acc[MB][NQ];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
 
-        wait_slabs(min(NST - 1, KT - 1));
+        wait_slabs(min(NSS - 1, NS - 1));
         lds_barrier();                   // slab 0 is in LDS; everybody has read this tile's ticket
         if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));             // ticket of the next tile
-        bf16x8 wf[2][4], xf[2][MB];
-        load_frags(wf[0], xf[0], 0, 0);
+        bf16x8 wf[2][NQ], xf[2][MB];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) load_frag_one(wf[0], xf[0], 0, 0, i);
 
-        auto slab = [&](int kt, auto issue_tag) __attribute__((always_inline)) {
-            constexpr bool ISSUE = decltype(issue_tag)::value;
-            const int stage = kt % NST;
+        // Slab s in buffer buf.  NEW: slab s + NSS exists (its slot 0 follows this slab's barrier); OLD: slab s - 1 + NSS
+        // exists (its later slots go out during this slab's K steps); FINAL: the tile's last slab.
+        auto slab = [&](int s, int buf, auto new_tag, auto old_tag, auto final_tag) __attribute__((always_inline)) {
+            constexpr bool NEW = decltype(new_tag)::value, OLD = decltype(old_tag)::value, FINAL = decltype(final_tag)::value;
+            const int nbuf = buf + 1 == NSS ? 0 : buf + 1;              // buffer of slab s + 1
+            const int pbuf = buf == 0 ? NSS - 1 : buf - 1;              // buffer slab s - 1 has left
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int cur = ks & 1, nxt = cur ^ 1;
-                bool copies = false;
-                if (ks + 1 < KS) {
-                    load_frags(wf[nxt], xf[nxt], stage, ks + 1);
-                } else if (ISSUE) {
-                    if (FP8) store_b_regs(tag, (kt + 1) % NST);
-                    wait_vmcnt<(NST - 2) * LPS>();
+            for (int u = 0; u < SUB; ++u) {
+                const int cur = u & 1, nxt = cur ^ 1;
+                const bool last = u + 1 == SUB;
+                // fragment reads of the next K step (from the next slab after the barrier) and this K step's share
+                // of the copies alternate in program order, so that the scheduler may interleave them with the MFMAs
+                int rbuf = buf, ru = u + 1;
+                const bool reads = !(last && FINAL);
+                if (last && !FINAL) {
+                    if (NEW) wait_vmcnt<(NSS - 2) * LPS>(); else wait_slabs(min(NSS - 2, NS - 2 - s));
                     lds_barrier();
-                    if (FP8) load_b_regs(tag, kt + 2);
-                    constexpr int NF = 4 + MB, NC = C::CA + (FP8 ? 0 : C::CB);
+                    rbuf = nbuf; ru = 0;
+                }
+                const int n = last ? (NEW ? C::S0 : 0) : (!OLD ? 0 : (u == 0 ? C::S1 : (u == 1 ? C::S2 : 0)));
+                const int c0 = last ? 0 : (u == 0 ? C::S0 : C::S0 + C::S1);
+                const int cslab = last ? s + NSS : s - 1 + NSS;
+                const int cbuf = last ? buf : pbuf;
 #pragma unroll
-                    for (int i = 0; i < (NF > NC ? NF : NC); ++i) {
-                        if (i < NF) load_frag_one(wf[nxt], xf[nxt], (kt + 1) % NST, 0, i);
-                        if (i < NC) issue_one(tag, kt + NST, stage, i);
-                    }
-                    copies = true;
-                } else if (kt + 1 < KT) {
-                    if (FP8) store_b_regs(tag, (kt + 1) % NST);
-                    wait_slabs(min(NST - 2, KT - 2 - kt));
-                    lds_barrier();
-                    load_frags(wf[nxt], xf[nxt], (kt + 1) % NST, 0);
-                    if (FP8 && kt + 2 < KT) load_b_regs(tag, kt + 2);
+                for (int i = 0; i < NMF; ++i) {
+                    if (i < NR && reads) load_frag_one(wf[nxt], xf[nxt], rbuf, ru, i);
+#pragma unroll
+                    for (int j = (i * n + NMF - 1) / NMF; j < ((i + 1) * n + NMF - 1) / NMF; ++j) issue_copy(tag, cslab, cbuf, c0 + j);
                 }
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
+                    for (int q = 0; q < NQ; ++q)
                         acc[mb][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][q], xf[cur][mb], acc[mb][q], 0, 0, 0);
-                constexpr int NMF = 4 * MB, NFR = 4 + MB, NCP = C::CA + C::CB;
-                if (copies) {
 #pragma unroll
-                    for (int i = 0; i < (NCP > NMF ? NCP : NMF); ++i) {
-                        if (i < NMF) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                        if (i < NFR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-                        if (i < NCP) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // slab copy
-                    }
-                } else {
+                for (int i = 0; i < NMF; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // MFMA
+                    if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                      // LDS read
 #pragma unroll
-                    for (int i = 0; i < NMF; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        if (i < NFR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    }
+                    for (int j = (i * n + NMF - 1) / NMF; j < ((i + 1) * n + NMF - 1) / NMF; ++j)
+                        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);                              // slab copy
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         {
-            int kt = 0;
-            for (; kt + NST < KT; ++kt) slab(kt, std::true_type{});
-            for (; kt < KT; ++kt) slab(kt, std::false_type{});
+            const std::true_type T{};
+            const std::false_type F{};
+            int buf = 0;
+            auto next = [&]() __attribute__((always_inline)) { buf = buf + 1 == NSS ? 0 : buf + 1; };
+            if (NSS < NS) slab(0, 0, T, F, F); else slab(0, 0, F, F, F);        // (every K here has at least 2 slabs)
+            next();
+            int s = 1;
+            for (; s + NSS < NS; ++s) { slab(s, buf, T, T, F); next(); }
+            if (s + 1 < NS && s - 1 + NSS < NS) { slab(s, buf, F, T, F); next(); ++s; }
+            for (; s + 1 < NS; ++s) { slab(s, buf, F, F, F); next(); }
+            slab(NS - 1, buf, F, F, T);
         }
-        lds_barrier();                   // every fragment is in registers: all stages are free; next ticket visible
+        lds_barrier();                   // every fragment is in registers: all buffers are free; next ticket visible
         const int em0 = m0, em_end = m_end, ent = nt;
-        const int nblk = s_ticket[0], nnt = s_ticket[1], ncls = s_ticket[2];
+        const int nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]), nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]),
+                  ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);    // uniform: keeps the copy descriptors in scalar registers
         if (nblk >= 0) start_tile(nblk, nnt, ncls);                     // the next tile's first slabs fly during the epilogue
 
         // ---- epilogue.  acc[mb][q][v]: row l31 of row block mb; column 8*(v>>2) + 4*lhi + (v&3) of column block q
@@ -723,7 +723,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
         if (ug < NU) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                const int m = em0 + wm * 64 + mb * 32 + l31;
+                const int m = em0 + wm * 32 * MB + mb * 32 + l31;
                 if (m < em_end) {
                     if (PHASE == 1) {
                         __bf16* out = a.h + (long long)m * a.f + ug * 128 + (wn & 1) * 64 + 4 * lhi;
@@ -739,7 +739,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
                     } else {
                         __bf16* out = a.y + (long long)m * a.d + ug * 256 + (wn & 1) * 128 + 4 * lhi;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                        for (int q = 0; q < NQ; ++q)
 #pragma unroll
                             for (int vg = 0; vg < 4; ++vg)
                                 *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
@@ -752,12 +752,12 @@ void ffn_adaptive_kernel(FfnArgs a) {
         return nblk >= 0 ? ncls : -1;
     };
 
-    int cls = s_ticket[2];
-    start_tile(s_ticket[0], s_ticket[1], cls);
+    int cls = __builtin_amdgcn_readfirstlane(s_ticket[2]);
+    start_tile(__builtin_amdgcn_readfirstlane(s_ticket[0]), __builtin_amdgcn_readfirstlane(s_ticket[1]), cls);
     while (cls >= 0) {
-        if (cls == 0)      cls = run_tile(std::integral_constant<int, 4>{});
-        else if (cls == 1) cls = run_tile(std::integral_constant<int, 2>{});
-        else               cls = run_tile(std::integral_constant<int, 1>{});
+        if (cls == 0)      cls = run_tile(std::integral_constant<int, 0>{});
+        else if (cls == 1) cls = run_tile(std::integral_constant<int, 1>{});
+        else               cls = run_tile(std::integral_constant<int, 2>{});
     }
 }
 
@@ -778,11 +778,11 @@ int num_cus() {
 }
 
 // Tile shapes.  ROWS = rows per tile:
-//   256: 8 wavefronts (4 x 2), 64 x 128 per wavefront, four 32-wide slabs of 32 KiB          (1 workgroup per CU)
+//   256: 8 wavefronts (4 x 2), 64 x 128 per wavefront, two 64-wide slabs of 64 KiB (whole cache lines per row; 1 workgroup per CU)
 //   128: 4 wavefronts (2 x 2), 64 x 128 per wavefront, three 32-wide slabs of 24 KiB         (2 workgroups per CU)
 //    64: 4 wavefronts (2 x 2), 32 x 128 per wavefront, three 32-wide slabs of 20 KiB         (2 workgroups per CU)
 template <int ROWS> struct Shape;
-template <> struct Shape<256> { static constexpr int WMW = 4, MB = 2, BK = 32, NST = 4, PER_CU = 1; };
+template <> struct Shape<256> { static constexpr int WMW = 4, MB = 2, BK = 64, NST = 2, PER_CU = 1; };
 template <> struct Shape<128> { static constexpr int WMW = 2, MB = 2, BK = 32, NST = 3, PER_CU = 2; };
 template <> struct Shape<64>  { static constexpr int WMW = 2, MB = 1, BK = 32, NST = 3, PER_CU = 2; };
 
@@ -804,10 +804,10 @@ moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     return k.done();
 }
 
-template <int PHASE, bool FP8>
+template <int PHASE>
 moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     static bool attr_done = false;
-    auto kern = ffn_adaptive_kernel<PHASE, FP8>;
+    auto kern = ffn_adaptive_kernel<PHASE>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ADAPTIVE_LDS);
         if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
@@ -820,11 +820,10 @@ moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s)
     return k.done();
 }
 
-template <bool FP8>
 moe_status launch_both_adaptive(const FfnArgs& a, long long max_blocks, hipStream_t s) {
-    moe_status st = launch_adaptive<1, FP8>(a, max_blocks * (a.f / 128), s);
+    moe_status st = launch_adaptive<1>(a, max_blocks * (a.f / 128), s);
     if (st != MOE_OK) return st;
-    return launch_adaptive<2, FP8>(a, max_blocks * (a.d / 256), s);
+    return launch_adaptive<2>(a, max_blocks * (a.d / 256), s);
 }
 
 template <int ROWS, bool FP8>
@@ -885,7 +884,7 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
     }
     const long long max_blocks = M / bm + G;
     const char* fixed = getenv("MOE_FFN_FIXED_SHAPE");
-    if (bm == 256 && !fp8 && !(fixed && fixed[0] == '1')) return launch_both_adaptive<false>(a, max_blocks, s);
+    if (bm == 256 && !fp8 && !(fixed && fixed[0] == '1')) return launch_both_adaptive(a, max_blocks, s);
     if (fp8) {
         if (bm == 256) return launch_both<256, true>(a, max_blocks, s);
         if (bm == 128) return launch_both<128, true>(a, max_blocks, s);
