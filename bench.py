@@ -160,6 +160,8 @@ def main():
     if not args.no_extras:
         result["extras"] = extras(moe, torch, np, workloads, dev)
         result["extras"].update(ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ffn_ws))
+        result["extras"]["makespan_model_us"] = makespan_extras(moe, np, cfg, traffic, g_out, b_out,
+                                                                result["extras"]["expert_time_us_vs_rows"])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r, x_h, W, M)
     print(json.dumps(result))
@@ -264,6 +266,30 @@ def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ff
         o = torch.tensor([0, rows] + [rows] * (E_loc - 1), dtype=torch.int32, device=dev)      # all rows on local expert 0
         curve[str(rows)] = timed(lambda: moe.moe_expert_ffn_sliced(x[:rows], o, 1, E_loc, wg, wu, wd, y=y[:rows], workspace=ffn_ws))
     out["expert_time_us_vs_rows"] = curve
+    return out
+
+
+def makespan_extras(moe, np, cfg, traffic, g_out, b_out, curve):
+    """Layer completion time of the two schedules under the analytic model of the paper's evaluation, with this GPU's
+    measured expert time against rows as the profiling-based cost (and a linear cost through the largest point),
+    a circuit of one xGMI link (153 GB/s), bf16 rows of d values, 10 ns reconfiguration."""
+    A = traffic.cpu().numpy()
+    rows = sorted(int(k) for k in curve)
+    table = dict(kind="table", rows=[float(k) for k in rows], seconds=[curve[str(k)] * 1e-6 for k in rows])
+    linear = dict(kind="linear", fixed=0.0, per_row=curve[str(rows[-1])] * 1e-6 / rows[-1])
+    out = {"assumptions": "153e9 B/s per circuit, %d B per row, 10 ns reconfiguration; residual of the capped schedule "
+                          "as one ideal round; profile = expert_time_us_vs_rows" % (2 * cfg.d)}
+    for name, o in (("greedy", g_out), ("bvn", b_out)):
+        K = int(o["counts"][0].item())
+        perms = o["perms"][0, :K].cpu().numpy()
+        dur = o["durations"][0, :K].cpu().numpy()
+        for mname, model in (("profile", table), ("linear", linear)):
+            args = (A, perms, dur, 2.0 * cfg.d, 153e9, 10e-9, model)
+            r = moe.moe_makespan_model(*args)
+            order = moe.moe_order_matchings(*args)
+            ro = moe.moe_makespan_model(*args, order=order)
+            out["%s_%s" % (name, mname)] = {"matchings": K, "no_overlap": r["sequential"] * 1e6, "overlap": r["overlap"] * 1e6,
+                                            "overlap_johnson_order": ro["overlap"] * 1e6, "ideal_all_to_all": r["ideal"] * 1e6}
     return out
 
 

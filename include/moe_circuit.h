@@ -141,6 +141,53 @@ moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, i
                                  void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_makespan_model -- Section 5 (Setup: "Execution time"), host-side.  Analytic completion time
+ * of one MoE layer (dispatch -> expert compute -> combine on all N ranks) under a circuit schedule:
+ * a matching occupies the network for reconf_s + duration * bytes_per_row / bandwidth (its largest
+ * transfer over the link bandwidth); a rank starts the rows of matching i when that dispatch has
+ * ended (and its previous rows are done) while the next dispatch proceeds; combine sends results
+ * back over the same pairs.  Conventions where the paper's simulator is not specified: matching t
+ * ships min(remaining entry, duration[t]) per pair; local rows (the diagonal) need no circuit and
+ * are computed first; what the schedule leaves is served as one round lasting (largest line sum of
+ * the residual) * bytes_per_row / bandwidth; the network serves all dispatches in order, then the
+ * combines in order, each once every rank has finished that slice.
+ * ALL POINTERS ARE HOST POINTERS; nothing is enqueued on the GPU.
+ *   traffic     in  int32 [N][N]  communication matrix (row = source), diagonal = local rows
+ *   perms       in  uint8 [K][N]  perms[t][i] = destination of source i in matching t
+ *   durations   in  int32 [K]     hold time of matching t in rows
+ *   order       in  int32 [K] or NULL: the matchings are played in this order (a permutation of
+ *                   0..K-1); amounts shipped are those of the original order
+ *   cost        in  see moe_cost_model
+ *   out         out double [MOE_MAKESPAN_FIELDS] seconds:
+ *                   [0] no overlap (every phase strictly after the other)   [1] with overlap
+ *                   [2] idealised congestion-free all-to-all, no overlap      [3] sum of network phases (one way)
+ *                   [4] sum over slices of the slowest rank's compute time
+ * moe_order_matchings -- Section 4 (ordering the matchings as a flow-shop problem): Johnson's rule
+ * for the two stages dispatch -> compute; writes the order into order_out int32 [K] (host).
+ * Errors: MOE_ERR_INVALID_ARG (NULL, N < 1, K < 0, bad cost model, order not a permutation),
+ * MOE_ERR_UNSUPPORTED_SHAPE (N > 256).
+ * ------------------------------------------------------------------------------------------- */
+#define MOE_COST_LINEAR 0   /* seconds = fixed_s + per_row_s * rows                                  */
+#define MOE_COST_TABLE  1   /* measured (rows, seconds) points, rows ascending; linear in between,
+                               the first point's time below it, the last segment continued above */
+#define MOE_MAKESPAN_FIELDS 5
+typedef struct moe_cost_model {
+    double bytes_per_row;    /* bytes a (token, expert) row occupies on the wire, e.g. 2 * d          */
+    double bandwidth;        /* bytes per second of one circuit                                       */
+    double reconf_s;         /* reconfiguration delay per change of matching, seconds                 */
+    int    kind;             /* MOE_COST_LINEAR or MOE_COST_TABLE; zero rows always cost nothing       */
+    double fixed_s, per_row_s;
+    const double* table_rows;     /* host [table_len] */
+    const double* table_seconds;  /* host [table_len] */
+    int    table_len;        /* >= 2 for MOE_COST_TABLE */
+} moe_cost_model;
+
+moe_status moe_makespan_model(const int32_t* traffic, int N, const uint8_t* perms, const int32_t* durations, int K,
+                              const int32_t* order, const moe_cost_model* cost, double* out);
+moe_status moe_order_matchings(const int32_t* traffic, int N, const uint8_t* perms, const int32_t* durations, int K,
+                               const moe_cost_model* cost, int32_t* order_out);
+
+/* ---------------------------------------------------------------------------------------------
  * Kernel timing (measurement aid).  While enabled, every kernel launch of this library is
  * bracketed by HIP events on the caller's stream.  moe_kernel_timing_read synchronises those
  * events, adds them up per kernel name and resets the table.

@@ -42,6 +42,9 @@ def _load():
         L.oracle_decompose_greedy.restype = ci
         L.oracle_decompose_bvn.argtypes = [i32p, ci, ci, ci, u8p, i32p, i32p, i32p, i32p]
         L.oracle_decompose_bvn.restype = ci
+        f64p = ctypes.POINTER(ctypes.c_double)
+        L.oracle_sinkhorn_bvn.argtypes = [i32p, ci, ci, ci, ci, ctypes.c_double, u8p, f64p, f64p, f64p, f64p]
+        L.oracle_sinkhorn_bvn.restype = ci
         L.oracle_decompose_batch.argtypes = [ci, i32p, ci, ci, ci, ci, u8p, i32p, i32p, i32p, i32p, u64p, ci]
         L.oracle_decompose_batch.restype = ci
         L.oracle_schedule_hash.argtypes = [u8p, i32p, ci, ci]
@@ -106,6 +109,25 @@ def decompose_bvn(A: np.ndarray, kmax: int | None = None, zero_diag: bool = Fals
     if c < 0:
         raise ValueError("oracle_decompose_bvn failed: %d" % c)
     return perms[:c].copy(), dur[:c].copy(), res, int(tot.value), pad
+
+
+def sinkhorn_bvn(A: np.ndarray, kmax: int | None = None, zero_diag: bool = False, iters: int = 100, eps: float = 1e-12):
+    """One matrix -> (perms, coefficients float64, scaled matrix, residual, deviation of the row sums from 1)."""
+    A = np.ascontiguousarray(A, dtype=np.int32)
+    n = A.shape[0]
+    if kmax is None:
+        kmax = n * n
+    perms = np.zeros((max(kmax, 1), n), dtype=np.uint8)
+    coef = np.zeros(max(kmax, 1), dtype=np.float64)
+    scaled = np.empty((n, n), dtype=np.float64)
+    res = np.empty((n, n), dtype=np.float64)
+    dev = ctypes.c_double(0.0)
+    c = _load().oracle_sinkhorn_bvn(_p(A, ctypes.c_int32), n, kmax, int(zero_diag), int(iters), float(eps),
+                                    _p(perms, ctypes.c_uint8), _p(coef, ctypes.c_double), _p(scaled, ctypes.c_double),
+                                    _p(res, ctypes.c_double), ctypes.byref(dev))
+    if c < 0:
+        raise ValueError("oracle_sinkhorn_bvn failed: %d" % c)
+    return perms[:c].copy(), coef[:c].copy(), scaled, res, float(dev.value)
 
 
 def decompose_batch(which: str, mats: np.ndarray, kmax: int, zero_diag: bool = False, nthreads: int = 1,

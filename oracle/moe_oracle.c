@@ -313,6 +313,86 @@ int oracle_decompose_bvn(const int32_t *A, int n, int kmax, int zero_diag,
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Sinkhorn-Knopp scaling followed by Birkhoff-von Neumann on the scaled matrix (Section 3.1:
+ * "a preprocessing step such as Sinkhorn-Knopp normalization is required before decomposition
+ * can be applied").  Double precision throughout.
+ *   X <- A (diagonal zeroed on request); `iters` times: every row with a positive sum is divided
+ *   by its sum, then every column with a positive sum by its sum (sums taken left to right / top
+ *   to bottom).  *deviation = max_i |row sum - 1| afterwards.
+ *   Then while fewer than kmax matchings: the support is {X > eps}; stop when it is empty or
+ *   holds no perfect matching (the scaling is approximate, so the last crumbs need not be
+ *   decomposable); sigma <- lexicographically smallest perfect matching of the support;
+ *   lambda <- min_i X[i][sigma(i)]; X[i][sigma(i)] -= lambda.
+ * scaled_out (may be NULL) receives X after the scaling, residual what is left at the end.
+ * The paper fixes neither the number of sweeps nor a tolerance: both are arguments.
+ * ------------------------------------------------------------------------------------------ */
+int oracle_sinkhorn_bvn(const int32_t *A, int n, int kmax, int zero_diag, int iters, double eps,
+                        uint8_t *perms, double *coeffs, double *scaled_out, double *residual,
+                        double *deviation)
+{
+    if (n <= 0 || n > ORACLE_MAX_N || kmax < 0 || iters < 0 || !(eps >= 0.0)) return -1;
+    double *X = residual;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j)
+            X[(size_t)i * n + j] = (zero_diag && i == j) ? 0.0 : (double)A[(size_t)i * n + j];
+    for (int it = 0; it < iters; ++it) {
+        for (int i = 0; i < n; ++i) {
+            double sum = 0.0;
+            for (int j = 0; j < n; ++j) sum += X[(size_t)i * n + j];
+            if (sum > 0.0) for (int j = 0; j < n; ++j) X[(size_t)i * n + j] = X[(size_t)i * n + j] / sum;
+        }
+        for (int j = 0; j < n; ++j) {
+            double sum = 0.0;
+            for (int i = 0; i < n; ++i) sum += X[(size_t)i * n + j];
+            if (sum > 0.0) for (int i = 0; i < n; ++i) X[(size_t)i * n + j] = X[(size_t)i * n + j] / sum;
+        }
+    }
+    double dev = 0.0;
+    for (int i = 0; i < n; ++i) {
+        double sum = 0.0;
+        for (int j = 0; j < n; ++j) sum += X[(size_t)i * n + j];
+        double d = sum > 1.0 ? sum - 1.0 : 1.0 - sum;
+        if (d > dev) dev = d;
+    }
+    if (deviation) *deviation = dev;
+    if (scaled_out) memcpy(scaled_out, X, sizeof(double) * (size_t)n * n);
+
+    unsigned char *support = (unsigned char *)malloc((size_t)n * n);
+    int row_to_col[ORACLE_MAX_N], col_to_row[ORACLE_MAX_N];
+    char seen[ORACLE_MAX_N];
+    for (int i = 0; i < n; ++i) { row_to_col[i] = -1; col_to_row[i] = -1; }
+    int count = 0, stuck = 0;
+    while (count < kmax && !stuck) {
+        int any = 0;
+        for (size_t x = 0; x < (size_t)n * n; ++x) { support[x] = X[x] > eps; any |= support[x]; }
+        if (!any) break;
+        for (int i = 0; i < n && !stuck; ++i) {
+            if (row_to_col[i] >= 0) continue;
+            memset(seen, 0, (size_t)n);
+            if (!kuhn_try(support, n, i, row_to_col, col_to_row, seen)) stuck = 1;
+        }
+        if (stuck) break;
+        lex_smallest_matching(support, n, row_to_col);
+        for (int i = 0; i < n; ++i) col_to_row[row_to_col[i]] = i;
+        double lambda = X[row_to_col[0]];
+        for (int i = 1; i < n; ++i) {
+            double x = X[(size_t)i * n + row_to_col[i]];
+            if (x < lambda) lambda = x;
+        }
+        for (int i = 0; i < n; ++i) {
+            perms[(size_t)count * n + i] = (uint8_t)row_to_col[i];
+            X[(size_t)i * n + row_to_col[i]] = X[(size_t)i * n + row_to_col[i]] - lambda;
+        }
+        coeffs[count] = lambda;
+        ++count;
+        for (int i = 0; i < n; ++i)
+            if (!(X[(size_t)i * n + row_to_col[i]] > eps)) { col_to_row[row_to_col[i]] = -1; row_to_col[i] = -1; }
+    }
+    free(support);
+    return count;
+}
+
+/* ------------------------------------------------------------------------------------------
  * Batched drivers (independent matrices), optionally spread over OpenMP threads.
  * perms may be NULL (only counts / durations / hashes wanted); scratch is then local.
  * ------------------------------------------------------------------------------------------ */

@@ -27,7 +27,7 @@ _STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAP
 EXPORTS = [
     "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
-    "moe_kernel_timing_read", "moe_last_hip_error",
+    "moe_kernel_timing_read", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings",
 ]
 
 _lib = None
@@ -35,6 +35,14 @@ _lib = None
 
 class MoeError(RuntimeError):
     pass
+
+
+class CostModel(ctypes.Structure):
+    """struct moe_cost_model of moe_circuit.h."""
+    _fields_ = [("bytes_per_row", ctypes.c_double), ("bandwidth", ctypes.c_double), ("reconf_s", ctypes.c_double),
+                ("kind", ctypes.c_int), ("fixed_s", ctypes.c_double), ("per_row_s", ctypes.c_double),
+                ("table_rows", ctypes.POINTER(ctypes.c_double)), ("table_seconds", ctypes.POINTER(ctypes.c_double)),
+                ("table_len", ctypes.c_int)]
 
 
 def build(verbose: bool = False) -> str:
@@ -88,6 +96,10 @@ def load():
     L.moe_kernel_timing_read.restype = ci
     L.moe_last_hip_error.argtypes = []
     L.moe_last_hip_error.restype = ctypes.c_char_p
+    L.moe_makespan_model.argtypes = [vp, ci, vp, vp, ci, vp, ctypes.POINTER(CostModel), ctypes.POINTER(ctypes.c_double)]
+    L.moe_makespan_model.restype = ci
+    L.moe_order_matchings.argtypes = [vp, ci, vp, vp, ci, ctypes.POINTER(CostModel), vp]
+    L.moe_order_matchings.restype = ci
     _lib = L
     return L
 
@@ -252,3 +264,59 @@ def moe_kernel_timing_read(cap: int = 32):
     if n < 0:
         _check(n, "moe_kernel_timing_read")
     return {names[i].decode(): (float(ms[i]), int(n_l[i])) for i in range(n)}
+
+
+# --------------------------------------------------------------------------------------------- host-side model
+def _cost_struct(bytes_per_row, bandwidth, reconf_s, model):
+    """model: dict(kind="linear", fixed=..., per_row=...) or dict(kind="table", rows=[...], seconds=[...])."""
+    import numpy as np
+    c = CostModel()
+    c.bytes_per_row, c.bandwidth, c.reconf_s = float(bytes_per_row), float(bandwidth), float(reconf_s)
+    keep = []
+    if model["kind"] == "linear":
+        c.kind, c.fixed_s, c.per_row_s, c.table_len = 0, float(model["fixed"]), float(model["per_row"]), 0
+    else:
+        xs = np.ascontiguousarray(model["rows"], dtype=np.float64)
+        ys = np.ascontiguousarray(model["seconds"], dtype=np.float64)
+        keep = [xs, ys]
+        c.kind, c.table_len = 1, len(xs)
+        c.table_rows = xs.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+        c.table_seconds = ys.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    return c, keep
+
+
+def _host_schedule(traffic, perms, durations):
+    import numpy as np
+    A = np.ascontiguousarray(traffic, dtype=np.int32)
+    P = np.ascontiguousarray(perms, dtype=np.uint8).reshape(-1, A.shape[0])
+    D = np.ascontiguousarray(durations, dtype=np.int32)
+    if P.shape[0] != D.shape[0]:
+        raise MoeError("perms and durations disagree on the number of matchings")
+    return A, P, D
+
+
+def moe_makespan_model(traffic, perms, durations, bytes_per_row, bandwidth, reconf_s, model, order=None):
+    """Host arrays (numpy) -> dict(sequential, overlap, ideal, comm, compute) in seconds."""
+    import numpy as np
+    A, P, D = _host_schedule(traffic, perms, durations)
+    c, keep = _cost_struct(bytes_per_row, bandwidth, reconf_s, model)
+    O = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+    out = (ctypes.c_double * 5)()
+    vp = ctypes.c_void_p
+    _check(load().moe_makespan_model(vp(A.ctypes.data), A.shape[0], vp(P.ctypes.data), vp(D.ctypes.data), P.shape[0],
+                                     None if O is None else vp(O.ctypes.data), ctypes.byref(c), out), "moe_makespan_model")
+    del keep
+    return dict(zip(("sequential", "overlap", "ideal", "comm", "compute"), [float(v) for v in out]))
+
+
+def moe_order_matchings(traffic, perms, durations, bytes_per_row, bandwidth, reconf_s, model):
+    """Host arrays (numpy) -> int32 [K] play order by Johnson's rule."""
+    import numpy as np
+    A, P, D = _host_schedule(traffic, perms, durations)
+    c, keep = _cost_struct(bytes_per_row, bandwidth, reconf_s, model)
+    order = np.zeros((P.shape[0],), dtype=np.int32)
+    vp = ctypes.c_void_p
+    _check(load().moe_order_matchings(vp(A.ctypes.data), A.shape[0], vp(P.ctypes.data), vp(D.ctypes.data), P.shape[0],
+                                      ctypes.byref(c), vp(order.ctypes.data)), "moe_order_matchings")
+    del keep
+    return order

@@ -21,3 +21,14 @@ def lib():
     import paper_2605_26845_amd as moe
     moe.load()
     return moe
+
+
+@pytest.fixture(scope="session")
+def hostlib():
+    """The binding for its host-only entry points (no GPU needed: nothing is enqueued)."""
+    import paper_2605_26845_amd as moe
+    import os
+    if not os.path.exists(moe._LIB_PATH):
+        moe.build()
+    moe.load()
+    return moe
