@@ -207,6 +207,21 @@ def extras(moe, torch, np, workloads, dev):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     out["bvn_128x128_full"] = {"matrices": Bb, "matrices_per_s": Bb / dt, "matchings_per_s": float(bb["counts"].sum().item()) / dt}
+    # the paper's own BvN pipeline (Sinkhorn-Knopp, then BvN in double precision) on dense 8 x 8 traffic (diagonal kept):
+    # its evaluation reports up to 50 matchings with many coefficients around 0.03
+    B8 = 4096
+    m8 = torch.from_numpy(workloads.random_matrices(B8, 8, seed=31, density=1.0, high=2000)).to(dev)
+    moe.moe_decompose_sinkhorn_bvn(m8[:8], 50, sweeps=100, want_perms=False, want_scaled=False, want_residual=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sk = moe.moe_decompose_sinkhorn_bvn(m8, 50, sweeps=100, want_perms=False, want_scaled=False, want_residual=False)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    cnt = sk["counts"].double()
+    coef = sk["coeffs"][sk["coeffs"] > 0]
+    out["sinkhorn_bvn_8x8_100_sweeps"] = {"matrices": B8, "matrices_per_s": B8 / dt, "matchings_per_s": float(cnt.sum().item()) / dt,
+                                          "mean_matchings": float(cnt.mean().item()), "median_coefficient": float(coef.median().item()),
+                                          "max_row_sum_deviation": float(sk["deviation"].max().item())}
     # histogram over 64 layers of the 64-rank top-8 routing shape (16 MiB of ids per layer)
     L, N, T, topk, E = 64, 64, 8192, 8, 256
     g = torch.Generator(device=dev)

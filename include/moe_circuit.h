@@ -95,6 +95,30 @@ moe_status moe_decompose_bvn(const int32_t* mats, int B, int N, int kmax, int fl
                              void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_decompose_sinkhorn_bvn -- Section 3.1 as the paper describes it: Sinkhorn-Knopp scaling
+ * towards a doubly stochastic matrix, then Birkhoff-von Neumann on the scaled matrix.  Double
+ * precision.  X <- A (diagonal zeroed with MOE_DECOMP_ZERO_DIAGONAL); `sweeps` times: every row
+ * with a positive sum is divided by its sum, then every column (sums taken in index order).  Then,
+ * while fewer than kmax matchings were emitted and {X > eps} holds a perfect matching: sigma <- the
+ * lexicographically smallest one; coefficient <- min_i X[i][sigma(i)]; X[i][sigma(i)] -= it.
+ * The paper gives neither a number of sweeps nor a tolerance; both are arguments.  The scaling is
+ * approximate (and cannot converge at all on a matrix without total support), so the loop may stop
+ * with crumbs left: they are returned in `residual`.
+ *   mats       in   int32 [B][N][N], entries >= 0
+ *   perms      out  uint8 [B][kmax][N]; may be NULL
+ *   coeffs     out  double [B][kmax]  the convex weights lambda_t; may be NULL
+ *   counts     out  int32 [B]
+ *   scaled     out  double [B][N][N]  X after the sweeps; may be NULL
+ *   residual   out  double [B][N][N]  X at exit; may be NULL
+ *   deviation  out  double [B]  max_i |row sum of the scaled matrix - 1|; may be NULL
+ * Limits as moe_decompose_greedy; sweeps >= 0, eps >= 0.  Results are bit-reproducible: every sum is
+ * taken in index order by one lane.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_decompose_sinkhorn_bvn(const int32_t* mats, int B, int N, int kmax, int flags, int sweeps, double eps,
+                                      uint8_t* perms, double* coeffs, int32_t* counts, double* scaled,
+                                      double* residual, double* deviation, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * moe_slice_table -- Sections 2.2 and 4.1: per matching a receiver hears from exactly one
  * source and its experts may start as soon as that batch has arrived.  For receiving rank r
  * this builds the row boundaries of the token batch each matching delivers.

@@ -27,7 +27,7 @@ _STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAP
 EXPORTS = [
     "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
-    "moe_kernel_timing_read", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings",
+    "moe_kernel_timing_read", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn",
 ]
 
 _lib = None
@@ -81,6 +81,8 @@ def load():
     L.moe_decompose_greedy.restype = ci
     L.moe_decompose_bvn.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     L.moe_decompose_bvn.restype = ci
+    L.moe_decompose_sinkhorn_bvn.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, vp, vp, vp]
+    L.moe_decompose_sinkhorn_bvn.restype = ci
     L.moe_slice_table_workspace_bytes.argtypes = [ci, ci, ci]
     L.moe_slice_table_workspace_bytes.restype = sz
     L.moe_slice_table.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, sz, vp]
@@ -192,6 +194,26 @@ def moe_decompose_bvn(mats, kmax: int, zero_diag: bool = False, want_perms=True,
     _check(load().moe_decompose_bvn(_ptr(mats), B, N, kmax, MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0,
                                     _ptr(o["perms"]), _ptr(o["durations"]), _ptr(o["counts"]), _ptr(o["residual"]),
                                     _ptr(o["pad_total"]), _ptr(o["hashes"]), _stream()), "moe_decompose_bvn")
+    return o
+
+
+def moe_decompose_sinkhorn_bvn(mats, kmax: int, zero_diag: bool = False, sweeps: int = 100, eps: float = 1e-12,
+                               want_perms=True, want_scaled=True, want_residual=True):
+    """mats int32 [B][N][N] -> dict(perms uint8 [B][kmax][N], coeffs float64 [B][kmax], counts, scaled, residual, deviation)."""
+    import torch
+    _dev_check(mats, torch.int32, "mats")
+    B, N, _ = mats.shape
+    dev = mats.device
+    o = dict(perms=torch.zeros((B, kmax, N), dtype=torch.uint8, device=dev) if want_perms else None,
+             coeffs=torch.zeros((B, kmax), dtype=torch.float64, device=dev),
+             counts=torch.zeros((B,), dtype=torch.int32, device=dev),
+             scaled=torch.empty((B, N, N), dtype=torch.float64, device=dev) if want_scaled else None,
+             residual=torch.empty((B, N, N), dtype=torch.float64, device=dev) if want_residual else None,
+             deviation=torch.zeros((B,), dtype=torch.float64, device=dev))
+    _check(load().moe_decompose_sinkhorn_bvn(_ptr(mats), B, N, kmax, MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0,
+                                             int(sweeps), float(eps), _ptr(o["perms"]), _ptr(o["coeffs"]), _ptr(o["counts"]),
+                                             _ptr(o["scaled"]), _ptr(o["residual"]), _ptr(o["deviation"]), _stream()),
+           "moe_decompose_sinkhorn_bvn")
     return o
 
 

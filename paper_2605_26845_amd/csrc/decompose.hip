@@ -158,8 +158,8 @@ __device__ __forceinline__ void store_matrix(const int32_t* R, int32_t* __restri
 
 // Adjacency masks: row-lane r gets {j : pred(R[r][j], r, j)}; built row by row with ballots so
 // that LDS reads are conflict free.
-template <int NPL, typename Pred>
-__device__ __forceinline__ void build_masks(const int32_t* R, int N, int lane, Mask<NPL> (&tm)[NPL], Pred pred) {
+template <int NPL, typename T, typename Pred>
+__device__ __forceinline__ void build_masks(const T* R, int N, int lane, Mask<NPL> (&tm)[NPL], Pred pred) {
 #pragma unroll
     for (int s = 0; s < NPL; ++s) tm[s].clear();
     for (int i = 0; i < N; ++i) {
@@ -463,7 +463,7 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             int vv[NPL];
 #pragma unroll
             for (int s = 0; s < NPL; ++s) vv[s] = v[s];
-            build_masks<NPL>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
+            build_masks<NPL, int32_t>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
         }
         lex_smallest<NPL>(tm, N, lane, sigma, p, 0);
         // ---- ship whole entries; the matching lasts as long as its heaviest pair
@@ -540,7 +540,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
 
     // ---- support masks and number of positive entries
     Mask<NPL> tm[NPL];
-    build_masks<NPL>(R, N, lane, tm, [](int x, int, int) { return x > 0; });
+    build_masks<NPL, int32_t>(R, N, lane, tm, [](int x, int, int) { return x > 0; });
     int nnz = 0;
 #pragma unroll
     for (int s = 0; s < NPL; ++s) {
@@ -663,6 +663,204 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
     if (residual) store_matrix(R, residual + (size_t)b * N * N, N, lane);
 }
 
+// ------------------------------------------------------------------------------ Sinkhorn-Knopp + floating-point BvN kernel
+// Section 3.1: the matrix is first scaled towards unit line sums, then decomposed.  Double precision; the scaled
+// matrix (N x N doubles, up to 128 KiB) lives in LDS.  Every sum runs in index order inside one lane (lane i owns
+// row i in the row sweep, lane j owns column j in the column sweep), every division is a plain IEEE division: the
+// result does not depend on how lanes are scheduled and can be reproduced bit for bit by a sequential program.
+__device__ __forceinline__ double wave_min_f64(double x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = fmin(x, __shfl_xor(x, off));
+    return x;
+}
+__device__ __forceinline__ double wave_max_f64(double x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = fmax(x, __shfl_xor(x, off));
+    return x;
+}
+
+template <int NPL>
+__global__ __launch_bounds__(MOE_WAVE)
+void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, int iters, double eps,
+                         uint8_t* __restrict__ perms, double* __restrict__ coeffs, int32_t* __restrict__ counts,
+                         double* __restrict__ scaled, double* __restrict__ residual, double* __restrict__ deviation) {
+    extern __shared__ double X[];
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x;
+    {
+        const int32_t* A = mats + (size_t)b * N * N;
+        const bool zd = flags & MOE_DECOMP_ZERO_DIAGONAL;
+        for (int x = lane; x < N * N; x += MOE_WAVE) X[x] = (zd && x / N == x % N) ? 0.0 : (double)A[x];
+        lds_fence();
+    }
+    // ---- Sinkhorn-Knopp sweeps: rows, then columns; a line whose sum is zero is left alone
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            const int i = lane + 64 * s;
+            if (i < N) {
+                double sum = 0.0;
+                for (int j = 0; j < N; ++j) sum += X[i * N + j];
+                if (sum > 0.0)
+                    for (int j = 0; j < N; ++j) X[i * N + j] = X[i * N + j] / sum;
+            }
+        }
+        lds_fence();
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            const int j = lane + 64 * s;
+            if (j < N) {
+                double sum = 0.0;
+                for (int i = 0; i < N; ++i) sum += X[i * N + j];
+                if (sum > 0.0)
+                    for (int i = 0; i < N; ++i) X[i * N + j] = X[i * N + j] / sum;
+            }
+        }
+        lds_fence();
+    }
+    {
+        double dev = 0.0;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            const int i = lane + 64 * s;
+            if (i < N) {
+                double sum = 0.0;
+                for (int j = 0; j < N; ++j) sum += X[i * N + j];
+                dev = fmax(dev, sum > 1.0 ? sum - 1.0 : 1.0 - sum);
+            }
+        }
+        dev = wave_max_f64(dev);
+        if (deviation && lane == 0) deviation[b] = dev;
+    }
+    if (scaled) {
+        double* out = scaled + (size_t)b * N * N;
+        for (int x = lane; x < N * N; x += MOE_WAVE) out[x] = X[x];
+    }
+
+    // ---- BvN on the scaled matrix: perfect matchings inside {X > eps}, repaired incrementally (as bvn_kernel)
+    Mask<NPL> tm[NPL];
+    build_masks<NPL, double>(X, N, lane, tm, [eps](double x, int, int) { return x > eps; });
+    int nnz = 0;
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) {
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) c += __popcll(tm[s].w[k]);
+        nnz += wave_sum(c);
+    }
+    int p[NPL], sigma[NPL];
+#pragma unroll
+    for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
+    uint8_t* perms_b = perms ? perms + (size_t)b * kmax * N : nullptr;
+    double* coef_b = coeffs ? coeffs + (size_t)b * kmax : nullptr;
+    int t = 0;
+    bool stuck = false;
+    while (t < kmax && nnz > 0 && !stuck) {
+        int first_row = N;
+        bool restricted_ok = true;
+        {
+            Mask<NPL> unmatched;
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) unmatched.w[s] = ballot64(lane + 64 * s < N && sigma[s] < 0);
+            while (unmatched.any() && restricted_ok) {
+                const int i = unmatched.first();
+                unmatched.reset(i);
+                first_row = min(first_row, i);
+                Mask<NPL> reached;
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) reached.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+                bool visited[NPL];
+                int parent[NPL];
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                const Mask<NPL> allowed = bcast_mask<NPL>(tm, i);
+                const int best = allowed.any() ? allowed.first() : -1;
+                for (int level = 0; level <= N; ++level) {
+                    if (best >= 0 && reached.test(best)) break;
+                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, i, visited, parent);
+                    if (!vm.any()) break;
+                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                }
+                Mask<NPL> hit = allowed & reached;
+                if (hit.any()) apply_path<NPL>(i, hit.first(), sigma, p, parent, lane, N);
+                else restricted_ok = false;
+            }
+        }
+        if (!restricted_ok) {
+            first_row = 0;
+            Mask<NPL> free_cols;
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+            while (free_cols.any() && !stuck) {
+                const int cf = free_cols.first();
+                free_cols.reset(cf);
+                Mask<NPL> reached;
+                reached.clear();
+                reached.set(cf);
+                bool visited[NPL];
+                int parent[NPL];
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                int target_row = -1;
+                for (int level = 0; level <= N; ++level) {
+                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, -1, visited, parent);
+                    if (!vm.any()) break;
+                    Mask<NPL> um;
+#pragma unroll
+                    for (int s = 0; s < NPL; ++s) um.w[s] = vm.w[s] & ballot64(sigma[s] < 0);
+                    if (um.any()) { target_row = um.first(); break; }
+                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                }
+                if (target_row < 0) { stuck = true; break; }      // the support holds no perfect matching: the scaling was approximate
+                apply_path<NPL>(target_row, bcast<NPL>(parent, target_row), sigma, p, parent, lane, N);
+            }
+        }
+        if (stuck) break;
+        lex_smallest<NPL>(tm, N, lane, sigma, p, first_row < N ? (restricted_ok ? first_row + 1 : 0) : N);
+        double x[NPL], lmin = 1.0e300;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            const int i = lane + 64 * s;
+            x[s] = i < N ? X[i * N + sigma[s]] : 1.0e300;
+            lmin = fmin(lmin, x[s]);
+        }
+        const double lambda = wave_min_f64(lmin);
+        if (perms_b) {
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) {
+                const int i = lane + 64 * s;
+                if (i < N) perms_b[(size_t)t * N + i] = (uint8_t)sigma[s];
+            }
+        }
+        if (coef_b && lane == 0) coef_b[t] = lambda;
+        ++t;
+        Mask<NPL> dead_rows;
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            const int i = lane + 64 * s;
+            bool dead = false;
+            if (i < N) {
+                const double nx = x[s] - lambda;
+                X[i * N + sigma[s]] = nx;
+                dead = !(nx > eps);
+            }
+            if (dead) { tm[s].reset(sigma[s]); sigma[s] = -1; }
+            dead_rows.w[s] = ballot64(dead);
+        }
+#pragma unroll
+        for (int s = 0; s < NPL; ++s) {
+            nnz -= __popcll(dead_rows.w[s]);
+            if (p[s] >= 0 && dead_rows.test(p[s])) p[s] = -1;
+        }
+        lds_fence();
+    }
+    if (lane == 0) counts[b] = t;
+    if (residual) {
+        double* out = residual + (size_t)b * N * N;
+        for (int x = lane; x < N * N; x += MOE_WAVE) out[x] = X[x];
+    }
+}
+
 moe_status check_args(const int32_t* mats, int B, int N, int kmax, int32_t* counts) {
     if (B < 0 || N < 1 || kmax < 0 || !counts) return MOE_ERR_INVALID_ARG;
     if (B > 0 && !mats) return MOE_ERR_INVALID_ARG;
@@ -705,5 +903,31 @@ extern "C" moe_status moe_decompose_bvn(const int32_t* mats, int B, int N, int k
     else
         hipLaunchKernelGGL(bvn_kernel<2>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts,
                            residual, pad_total, (unsigned long long*)hashes);
+    return k.done();
+}
+
+extern "C" moe_status moe_decompose_sinkhorn_bvn(const int32_t* mats, int B, int N, int kmax, int flags, int sweeps, double eps,
+                                                 uint8_t* perms, double* coeffs, int32_t* counts, double* scaled,
+                                                 double* residual, double* deviation, void* hip_stream) {
+    moe_status st = check_args(mats, B, N, kmax, counts);
+    if (st != MOE_OK) return st;
+    if (sweeps < 0 || !(eps >= 0.0)) return MOE_ERR_INVALID_ARG;
+    if (B == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t lds = (size_t)N * N * sizeof(double);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)sinkhorn_bvn_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           MOE_MAX_RANKS * MOE_MAX_RANKS * (int)sizeof(double));
+        if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
+        attr_done = true;
+    }
+    moe::LaunchScope k("sinkhorn_bvn_kernel", s);
+    if (N <= 64)
+        hipLaunchKernelGGL(sinkhorn_bvn_kernel<1>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, sweeps, eps, perms,
+                           coeffs, counts, scaled, residual, deviation);
+    else
+        hipLaunchKernelGGL(sinkhorn_bvn_kernel<2>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, sweeps, eps, perms,
+                           coeffs, counts, scaled, residual, deviation);
     return k.done();
 }

@@ -152,6 +152,51 @@ def test_decompose_stress_matrices_128(lib):
     check_decomposition(lib, "bvn", mats[:2], oracle.bvn_bound(128), True)
 
 
+def check_sinkhorn(lib, mats, kmax, zero_diag, sweeps, eps):
+    """Bit-exact: both sides add in index order and divide in IEEE double precision."""
+    B, N, _ = mats.shape
+    out = lib.moe_decompose_sinkhorn_bvn(dev(mats), kmax, zero_diag=zero_diag, sweeps=sweeps, eps=eps)
+    torch.cuda.synchronize()
+    counts = out["counts"].cpu().numpy()
+    perms, coef = out["perms"].cpu().numpy(), out["coeffs"].cpu().numpy()
+    scaled, resid, devi = out["scaled"].cpu().numpy(), out["residual"].cpu().numpy(), out["deviation"].cpu().numpy()
+    for b in range(B):
+        rp, rc, rx, rr, rd = oracle.sinkhorn_bvn(mats[b], kmax=kmax, zero_diag=zero_diag, iters=sweeps, eps=eps)
+        assert np.array_equal(scaled[b], rx), (N, b, np.abs(scaled[b] - rx).max())
+        assert devi[b] == rd
+        assert counts[b] == len(rp), (N, b, counts[b], len(rp))
+        assert np.array_equal(perms[b, :len(rp)], rp), (N, b)
+        assert np.array_equal(coef[b, :len(rp)], rc), (N, b)
+        assert np.array_equal(resid[b], rr), (N, b)
+        assert (coef[b, len(rp):] == 0).all()
+
+
+@pytest.mark.parametrize("N,density,high", [(1, 1.0, 5), (2, 1.0, 3), (5, 0.7, 9), (8, 1.0, 1000), (16, 0.6, 300), (33, 0.5, 50),
+                                            (64, 1.0, 5000), (65, 0.6, 20), (128, 0.7, 40000)])
+@pytest.mark.parametrize("zero_diag", [False, True])
+def test_sinkhorn_bvn_random(lib, N, density, high, zero_diag):
+    say("sinkhorn bvn random", N, density, high, zero_diag)
+    nb = 4 if N <= 65 else 2
+    mats = workloads.random_matrices(nb, N, seed=2900 + N, density=density, high=high)
+    mats[1] = 0
+    check_sinkhorn(lib, mats, 4, zero_diag, sweeps=20, eps=1e-12)
+    check_sinkhorn(lib, mats, min(N * N, 700), zero_diag, sweeps=60 if N <= 65 else 25, eps=1e-12)
+    check_sinkhorn(lib, mats[:1], 10, zero_diag, sweeps=0, eps=0.5)              # no scaling at all: plain BvN steps on A
+
+
+def test_sinkhorn_bvn_configs_and_errors(lib):
+    say("sinkhorn bvn configs")
+    for name in ("tiny", "c2", "c3"):
+        cfg = workloads.CONFIGS[name]
+        traffic, _ = oracle.route_histogram(workloads.config_routing(cfg), cfg.E)
+        for zd in (False, True):
+            check_sinkhorn(lib, traffic[None], oracle.bvn_bound(cfg.N), zd, sweeps=200, eps=1e-12)
+    with pytest.raises(lib.MoeError):
+        lib.moe_decompose_sinkhorn_bvn(torch.zeros((1, 4, 4), dtype=torch.int32, device=DEV), 4, sweeps=-1)
+    with pytest.raises(lib.MoeError):
+        lib.moe_decompose_sinkhorn_bvn(torch.zeros((1, 129, 129), dtype=torch.int32, device=DEV), 4)
+
+
 # ------------------------------------------------------------------------------ slice table
 @pytest.mark.parametrize("name,which", [("tiny", "greedy"), ("tiny", "bvn"), ("c2", "greedy"), ("c2", "bvn"), ("c3", "greedy")])
 def test_slice_table(lib, name, which):
