@@ -272,6 +272,14 @@ def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ff
             moe.moe_expert_ffn_sliced(xs, o, 1, E_loc, wg, wu, wd, y=ys, workspace=ffn_ws)
 
     out["ffn_one_call_us"] = one_call
+    # the same call with the dispatch gather / combine scatter fused in: rows in a random arrival order, router weights
+    g = torch.Generator(device=dev)
+    g.manual_seed(3)
+    M_used = int(off_h[-1])
+    row_map = torch.randperm(M_used, device=dev, generator=g).to(torch.int32)
+    gate = torch.rand((M_used,), device=dev, generator=g)
+    out["ffn_one_call_row_map_us"] = timed(lambda: moe.moe_expert_ffn_sliced_mapped(x, offsets, S, E_loc, wg, wu, wd, row_map,
+                                                                                    gate, y=y, workspace=ffn_ws))
     out["ffn_one_call_per_slice_us"] = timed(run_slices)
     out["ffn_slices"] = len(per_slice)
     curve = {}

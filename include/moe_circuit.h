@@ -141,6 +141,25 @@ moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk, int E, in
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_slice_table_rows -- moe_slice_table plus the row map that turns "dispatch" into a gather
+ * (Section 2.1: dispatch sends each token to its experts, combine returns the results): rows
+ * reach rank r source by source, each source in its (token, slot) order; the schedule wants them
+ * slice by slice.  For every schedule row m in [0, offsets[last]) (slice-major, then local
+ * expert, then source rank, then arrival order):
+ *   row_arrival[m]     = position of that assignment in the arrival order (0 .. M-1)
+ *   row_assignment[m]  = s * T * topk + t * topk + slot, its index in ids
+ * Either output may be NULL (not both).  Other arguments as moe_slice_table; workspace of
+ * moe_slice_table_rows_workspace_bytes(N, kmax, E) bytes.
+ * Limits: as moe_slice_table, and (kmax + 1) * E_loc <= 8192, E_loc <= 64.
+ * ------------------------------------------------------------------------------------------- */
+size_t     moe_slice_table_rows_workspace_bytes(int N, int kmax, int E);
+moe_status moe_slice_table_rows(const int32_t* ids, int N, int T, int topk, int E, int r,
+                                const int32_t* traffic, const uint8_t* perms, const int32_t* durations,
+                                const int32_t* count, int kmax, int32_t* offsets,
+                                int32_t* row_arrival, int32_t* row_assignment,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * moe_expert_ffn_sliced -- Section 2.1 (compute: each expert processes its assigned tokens),
  * issued for all slices of a schedule at once so that no launch is paid per matching
  * (Section 2.2: fixed launch / synchronisation overheads dominate small batches).
@@ -163,6 +182,26 @@ moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, i
                                  const void* w_gate, const void* w_up, const void* w_down,
                                  const float* s_gate, const float* s_up, const float* s_down,
                                  void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_expert_ffn_sliced_mapped -- moe_expert_ffn_sliced with the dispatch gather and the combine
+ * scatter fused into the kernels (Section 2.1: dispatch / compute / combine): schedule row m reads
+ * x[row_map[m]] (the gather happens in the copy that stages the operand tile) and its result goes
+ * to y[row_map[m]], multiplied by row_gate[m] (the router weight of that (token, expert) pair) in
+ * fp32 before the rounding to bf16:
+ *     y[row_map[m]] = row_gate[m] * ( silu(x[row_map[m]] Wg_e^T) * (x[row_map[m]] Wu_e^T) ) Wd_e^T
+ *   row_map    in   int32 [offsets[last]], a permutation of 0 .. offsets[last]-1 (e.g. row_arrival
+ *                   of moe_slice_table_rows); NULL = identity
+ *   row_gate   in   float [offsets[last]]; NULL = 1
+ *   x, y            bf16 [M][d] in arrival order
+ * Everything else as moe_expert_ffn_sliced.  Values of row_map outside [0, M) are not checked.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t* offsets, int M, int S, int E_loc,
+                                        int d, int f, int weight_format,
+                                        const void* w_gate, const void* w_up, const void* w_down,
+                                        const float* s_gate, const float* s_up, const float* s_down,
+                                        const int32_t* row_map, const float* row_gate,
+                                        void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
  * moe_makespan_model -- Section 5 (Setup: "Execution time"), host-side.  Analytic completion time

@@ -85,3 +85,23 @@ def expert_ffn_sliced(x_bits: np.ndarray, offsets: np.ndarray, E_loc: int, weigh
         if return_hidden:
             h_all[sel] = h
     return (y, h_all) if return_hidden else y
+
+
+def expert_ffn_sliced_mapped(x_bits: np.ndarray, offsets: np.ndarray, E_loc: int, weights, row_map: np.ndarray,
+                             row_gate: np.ndarray | None = None, rows: np.ndarray | None = None):
+    """Dispatch gather and combine scatter around the expert FFN (Section 2.1): schedule row m is row row_map[m] of
+    x (arrival order) and of the result, which is multiplied by the router weight row_gate[m].
+    Returns (y float64[len(rows) or M_used][d], target rows): y[k] belongs at row target[k] of the output."""
+    offsets = np.asarray(offsets, dtype=np.int64)
+    M_used = int(offsets[-1])
+    row_map = np.asarray(row_map, dtype=np.int64)
+    assert len(row_map) >= M_used
+    if rows is None:
+        rows = np.arange(M_used, dtype=np.int64)
+    rows = np.asarray(rows, dtype=np.int64)
+    gathered = np.zeros((M_used, x_bits.shape[1]), dtype=np.uint16)
+    gathered[rows] = x_bits[row_map[rows]]
+    y = expert_ffn_sliced(gathered, offsets, E_loc, weights, rows=rows)
+    if row_gate is not None:
+        y = y * np.asarray(row_gate, dtype=np.float32).astype(np.float64)[rows, None]
+    return y, row_map[rows]

@@ -27,7 +27,8 @@ _STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAP
 EXPORTS = [
     "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
-    "moe_kernel_timing_read", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn",
+    "moe_kernel_timing_read", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
+    "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped",
 ]
 
 _lib = None
@@ -87,6 +88,12 @@ def load():
     L.moe_slice_table_workspace_bytes.restype = sz
     L.moe_slice_table.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, sz, vp]
     L.moe_slice_table.restype = ci
+    L.moe_slice_table_rows_workspace_bytes.argtypes = [ci, ci, ci]
+    L.moe_slice_table_rows_workspace_bytes.restype = sz
+    L.moe_slice_table_rows.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
+    L.moe_slice_table_rows.restype = ci
+    L.moe_expert_ffn_sliced_mapped.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_expert_ffn_sliced_mapped.restype = ci
     L.moe_ffn_workspace_bytes.argtypes = [ci, ci, ci]
     L.moe_ffn_workspace_bytes.restype = sz
     L.moe_expert_ffn_sliced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -237,12 +244,48 @@ def moe_slice_table(ids, E: int, r: int, traffic, perms, durations, count, kmax:
     return offsets
 
 
+def moe_slice_table_rows(ids, E: int, r: int, traffic, perms, durations, count, kmax: int, M: int, offsets=None,
+                         want_arrival=True, want_assignment=True, workspace=None):
+    """moe_slice_table plus the row map: -> (offsets, row_arrival int32 [M] or None, row_assignment int32 [M] or None);
+    M = number of assignments destined to r (column sum of traffic)."""
+    import torch
+    _dev_check(ids, torch.int32, "ids")
+    _dev_check(traffic, torch.int32, "traffic")
+    _dev_check(perms, torch.uint8, "perms")
+    _dev_check(durations, torch.int32, "durations")
+    _dev_check(count, torch.int32, "count")
+    N, T, topk = ids.shape
+    e_loc = E // N
+    if offsets is None:
+        offsets = torch.empty(((kmax + 2) * e_loc + 1,), dtype=torch.int32, device=ids.device)
+    arr = torch.full((M,), -1, dtype=torch.int32, device=ids.device) if want_arrival else None
+    asg = torch.full((M,), -1, dtype=torch.int32, device=ids.device) if want_assignment else None
+    need = load().moe_slice_table_rows_workspace_bytes(N, kmax, E)
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=ids.device)
+    _check(load().moe_slice_table_rows(_ptr(ids), N, T, topk, E, r, _ptr(traffic), _ptr(perms), _ptr(durations), _ptr(count),
+                                       kmax, _ptr(offsets), _ptr(arr), _ptr(asg), _ptr(workspace), workspace.numel(),
+                                       _stream()), "moe_slice_table_rows")
+    return offsets, arr, asg
+
+
 def moe_ffn_workspace_bytes(M: int, d: int, f: int) -> int:
     return int(load().moe_ffn_workspace_bytes(M, d, f))
 
 
+def moe_expert_ffn_sliced_mapped(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, row_map, row_gate=None,
+                                 s_gate=None, s_up=None, s_down=None, y=None, workspace=None):
+    """As moe_expert_ffn_sliced with x and y in arrival order: schedule row m is row row_map[m] of both, and its
+    result is scaled by row_gate[m]."""
+    import torch
+    _dev_check(row_map, torch.int32, "row_map")
+    _dev_check(row_gate, torch.float32, "row_gate")
+    return moe_expert_ffn_sliced(x, offsets, S, E_loc, w_gate, w_up, w_down, s_gate, s_up, s_down, y, workspace,
+                                 _row_map=row_map, _row_gate=row_gate)
+
+
 def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down=None,
-                          y=None, workspace=None):
+                          y=None, workspace=None, _row_map=None, _row_gate=None):
     """x bf16 [M][d]; offsets int32 [S*E_loc+1]; bf16 weights (w_gate,w_up [E_loc][f][d], w_down [E_loc][d][f]) or
     uint8 E4M3 codes with float32 block scales -> y bf16 [M][d]."""
     import torch
@@ -266,6 +309,13 @@ def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, 
     need = moe_ffn_workspace_bytes(M, d, f)
     if workspace is None:
         workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=x.device)
+    if _row_map is not None or _row_gate is not None:
+        _check(load().moe_expert_ffn_sliced_mapped(_ptr(x), _ptr(offsets), M, S, E_loc, d, f,
+                                                   MOE_W_FP8_E4M3_B128 if fp8 else MOE_W_BF16, _ptr(w_gate), _ptr(w_up),
+                                                   _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(_row_map),
+                                                   _ptr(_row_gate), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
+               "moe_expert_ffn_sliced_mapped")
+        return y
     _check(load().moe_expert_ffn_sliced(_ptr(x), _ptr(offsets), M, S, E_loc, d, f,
                                         MOE_W_FP8_E4M3_B128 if fp8 else MOE_W_BF16, _ptr(w_gate), _ptr(w_up),
                                         _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(y), _ptr(workspace),

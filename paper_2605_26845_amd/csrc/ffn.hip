@@ -37,7 +37,11 @@ struct FfnArgs {
     const float *sg, *su, *sd;         // block scales (fp8) or null
     int4* plan;                        // plan[0].x = number of row blocks; plan[PLAN_HDR + i] = (row0, row_end, expert, class)
     int d, f;
+    const int32_t* row_map;            // [M] or null: row m of the schedule is row row_map[m] of x and of y
+    const float* row_gate;             // [M] or null: y row is scaled by row_gate[m]
 };
+// row of x that schedule row m reads (phase 1) / row of y it writes (phase 2)
+__device__ __forceinline__ int mapped_row(const FfnArgs& a, int m) { return a.row_map ? a.row_map[m] : m; }
 
 // ---------------------------------------------------------------------------------- plan kernel
 // Splits every group into row blocks of BM rows.  One workgroup.  Malformed offsets cannot make
@@ -245,7 +249,10 @@ void ffn_gemm_kernel(FfnArgs a) {
         const int e = info.z;
         const int rows = min(BM, m_end - m0);
 #pragma unroll
-        for (int i = 0; i < CA; ++i) a_off[i] = (m0 + min(row0 + RS * i, rows - 1)) * K + kcg * 8;
+        for (int i = 0; i < CA; ++i) {
+            const int m = m0 + min(row0 + RS * i, rows - 1);
+            a_off[i] = (PHASE == 1 ? mapped_row(a, m) : m) * K + kcg * 8;
+        }
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
             constexpr int PER_HALF = 128 / RS;                            // passes per 128 slab rows
@@ -441,13 +448,15 @@ void ffn_gemm_kernel(FfnArgs a) {
                             *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
                         }
                 } else {
-                    __bf16* out = a.y + (long long)m * a.d + ent * BN + wn * 128 + 4 * lhi;
+                    __bf16* out = a.y + (long long)mapped_row(a, m) * a.d + ent * BN + wn * 128 + 4 * lhi;
+                    const float gate = a.row_gate ? a.row_gate[m] : 1.0f;
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int vg = 0; vg < 4; ++vg)
                             *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
-                                pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
+                                pack4(gate * acc[mb][q][vg * 4], gate * acc[mb][q][vg * 4 + 1], gate * acc[mb][q][vg * 4 + 2],
+                                      gate * acc[mb][q][vg * 4 + 3]);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
@@ -562,7 +571,10 @@ void ffn_adaptive_kernel(FfnArgs a) {
         const int rows = min(C::BMc, m_end - m0);
         const int row0 = C::ROWB == 128 ? row0_128 : row0_64, kcg = C::ROWB == 128 ? kcg_128 : kcg_64;
 #pragma unroll
-        for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)((m0 + min(row0 + C::RPC * i, rows - 1)) * K + kcg * 8) * 2u;
+        for (int i = 0; i < C::CA; ++i) {
+            const int m = m0 + min(row0 + C::RPC * i, rows - 1);
+            a_voff[i] = (unsigned int)((PHASE == 1 ? mapped_row(a, m) : m) * K + kcg * 8) * 2u;
+        }
         if (PHASE == 1) {
             wB = (unsigned long long)((const __bf16*)a.wg + (size_t)e * a.f * K);
             wB_up = (unsigned long long)((const __bf16*)a.wu + (size_t)e * a.f * K) - wB;
@@ -737,13 +749,15 @@ void ffn_adaptive_kernel(FfnArgs a) {
                                 *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
                             }
                     } else {
-                        __bf16* out = a.y + (long long)m * a.d + ug * 256 + (wn & 1) * 128 + 4 * lhi;
+                        __bf16* out = a.y + (long long)mapped_row(a, m) * a.d + ug * 256 + (wn & 1) * 128 + 4 * lhi;
+                        const float gate = a.row_gate ? a.row_gate[m] : 1.0f;
 #pragma unroll
                         for (int q = 0; q < NQ; ++q)
 #pragma unroll
                             for (int vg = 0; vg < 4; ++vg)
                                 *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
-                                    pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
+                                    pack4(gate * acc[mb][q][vg * 4], gate * acc[mb][q][vg * 4 + 1], gate * acc[mb][q][vg * 4 + 2],
+                                          gate * acc[mb][q][vg * 4 + 3]);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -840,10 +854,11 @@ extern "C" size_t moe_ffn_workspace_bytes(int M, int d, int f) {
     return h_bytes(M, f) + (size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4);
 }
 
-extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, int S, int E_loc, int d, int f,
-                                            int weight_format, const void* w_gate, const void* w_up, const void* w_down,
-                                            const float* s_gate, const float* s_up, const float* s_down, void* y,
-                                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t* offsets, int M, int S, int E_loc, int d, int f,
+                                                   int weight_format, const void* w_gate, const void* w_up, const void* w_down,
+                                                   const float* s_gate, const float* s_up, const float* s_down,
+                                                   const int32_t* row_map, const float* row_gate, void* y,
+                                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (M < 0 || S < 0 || E_loc < 1 || d < 1 || f < 1 || !offsets) return MOE_ERR_INVALID_ARG;
     if (weight_format != MOE_W_BF16 && weight_format != MOE_W_FP8_E4M3_B128) return MOE_ERR_INVALID_ARG;
     if (!w_gate || !w_up || !w_down) return MOE_ERR_INVALID_ARG;
@@ -875,6 +890,7 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
     int4* plan = (int4*)((char*)workspace + h_bytes(M, f));
     a.plan = plan;
     a.d = d; a.f = f;
+    a.row_map = row_map; a.row_gate = row_gate;
     {
         moe::LaunchScope k("ffn_plan_kernel", s);
         hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, (int)G, E_loc, M, bm,
@@ -893,4 +909,12 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
     if (bm == 256) return launch_both<256, false>(a, max_blocks, s);
     if (bm == 128) return launch_both<128, false>(a, max_blocks, s);
     return launch_both<64, false>(a, max_blocks, s);
+}
+
+extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, int S, int E_loc, int d, int f,
+                                            int weight_format, const void* w_gate, const void* w_up, const void* w_down,
+                                            const float* s_gate, const float* s_up, const float* s_down, void* y,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return moe_expert_ffn_sliced_mapped(x, offsets, M, S, E_loc, d, f, weight_format, w_gate, w_up, w_down, s_gate, s_up,
+                                        s_down, nullptr, nullptr, y, workspace, workspace_bytes, hip_stream);
 }

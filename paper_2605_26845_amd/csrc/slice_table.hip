@@ -56,7 +56,10 @@ __global__ __launch_bounds__(ST_THREADS)
 void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E, int e_loc, int r,
                      const int32_t* __restrict__ traffic, const uint8_t* __restrict__ perms,
                      const int32_t* __restrict__ durations, const int32_t* __restrict__ count_ptr, int kmax,
-                     int32_t* __restrict__ sizes, int2* __restrict__ win_ws) {
+                     int32_t* __restrict__ sizes, int2* __restrict__ win_ws, int32_t* __restrict__ wcnt_ws,
+                     int32_t* __restrict__ res_cnt, int32_t* __restrict__ wcount) {
+    // wcnt_ws / res_cnt / wcount (all or none; only with (kmax+1)*e_loc <= CNT_CAP): per source the counts per
+    // (window, expert), the counts of what was not shipped, and the number of windows -- what st_place_kernel needs
     __shared__ ScanSmem sm;
     __shared__ int2 lds_win[WIN_CAP];
     __shared__ int lds_cnt[CNT_CAP];
@@ -128,6 +131,12 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
     }
     if (cnt_in_lds) {
         __syncthreads();
+        if (wcnt_ws) {
+            int32_t* mine_ws = wcnt_ws + (size_t)s * (kmax + 1) * e_loc;
+            for (int x = tid; x < (W + 1) * e_loc; x += ST_THREADS) mine_ws[x] = lds_cnt[x];
+            if (tid < e_loc) res_cnt[(size_t)s * e_loc + tid] = s == r ? 0 : lds_cnt[W * e_loc + tid];
+            if (tid == 0) wcount[s] = W;
+        }
         for (int x = tid; x < (W + 1) * e_loc; x += ST_THREADS) {
             int c = lds_cnt[x];
             if (c == 0) continue;
@@ -135,6 +144,99 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
             int slice = s == r ? 0 : (w < W ? (win_in_lds ? lds_win[w].x : my_ws[w].x) : kmax + 1);
             atomicAdd(&sizes[(size_t)slice * e_loc + el], c);
         }
+    }
+}
+
+// Row map of the receiving rank: for every row of the schedule (slice-major, then local expert, then source, then
+// arrival order) its arrival index (position among the assignments destined to r, sources in rank order, each in
+// its (token, slot) order) and its assignment index s * T * topk + t * topk + slot.  One workgroup per source walks
+// the source's assignments as st_count_kernel did.  Windows are consecutive stretches of the arrival order, so the
+// rank of an assignment inside its (window, expert) group is the number of earlier assignments of that expert minus
+// those that fell into earlier windows; what no matching shipped is appended source by source.
+constexpr int PLACE_MAX_ELOC = 64;
+__global__ __launch_bounds__(ST_THREADS)
+void st_place_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E, int e_loc, int r,
+                     const int32_t* __restrict__ traffic, int kmax, const int32_t* __restrict__ offsets,
+                     const int2* __restrict__ win_ws, const int32_t* __restrict__ wcnt_ws, const int32_t* __restrict__ res_cnt,
+                     const int32_t* __restrict__ wcount, int32_t* __restrict__ row_arrival, int32_t* __restrict__ row_assignment) {
+    __shared__ ScanSmem sm;
+    __shared__ int2 lds_win[WIN_CAP];
+    __shared__ int pre[CNT_CAP];                       // assignments of expert el in windows before w, at [w * e_loc + el]
+    __shared__ int cntw[ST_WAVES][PLACE_MAX_ELOC];     // this chunk: assignments of expert el seen by wavefront w
+    __shared__ int run_el[PLACE_MAX_ELOC], res_base[PLACE_MAX_ELOC];
+    __shared__ int src_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s = blockIdx.x;
+    const int W = wcount[s];
+    const int2* my_ws = win_ws + (size_t)s * kmax;
+    const bool win_in_lds = W <= WIN_CAP;
+    for (int x = tid; x < W && x < WIN_CAP; x += ST_THREADS) lds_win[x] = my_ws[x];
+    if (tid < e_loc) {
+        const int32_t* c = wcnt_ws + (size_t)s * (kmax + 1) * e_loc;
+        int acc = 0;
+        for (int w = 0; w <= W; ++w) { pre[w * e_loc + tid] = acc; acc += c[w * e_loc + tid]; }
+        int rb = 0;
+        for (int s2 = 0; s2 < s; ++s2) rb += res_cnt[(size_t)s2 * e_loc + tid];
+        res_base[tid] = rb;
+        run_el[tid] = 0;
+    }
+    if (tid == 0) {
+        int b = 0;
+        for (int s2 = 0; s2 < s; ++s2) b += traffic[(size_t)s2 * N + r];
+        src_base = b;
+    }
+    cntw[wave][lane] = 0;
+    __syncthreads();
+
+    int q_base = 0;
+    const int32_t* src = ids + (size_t)s * per_src;
+    for (int x0 = 0; x0 < per_src; x0 += ST_THREADS) {
+        const int x = x0 + tid;
+        const int e = x < per_src ? src[x] : -1;
+        const bool mine = (unsigned)e < (unsigned)E && e / e_loc == r;
+        int excl, tot;
+        unsigned long long dummy_i, dummy_t;
+        block_scan(sm, mine, 0ULL, tid, excl, dummy_i, tot, dummy_t);
+        const int el = mine ? e % e_loc : 0;
+        // rank among this wavefront's assignments of the same expert, and the wavefront's count per expert
+        int rank_w = 0;
+        unsigned long long todo = __ballot(mine);
+        while (todo) {
+            const int leader = __builtin_ctzll(todo);
+            const int k = __builtin_amdgcn_readlane(el, leader);
+            const unsigned long long peers = __ballot(mine && el == k);
+            if (mine && el == k) rank_w = __popcll(peers & ((1ULL << lane) - 1ULL));
+            if (lane == leader) cntw[wave][k] = __popcll(peers);
+            todo &= ~peers;
+        }
+        __syncthreads();
+        int before = 0;
+        if (mine) {
+            before = run_el[el] + rank_w;
+            for (int w = 0; w < wave; ++w) before += cntw[w][el];
+        }
+        __syncthreads();
+        if (tid < PLACE_MAX_ELOC) {
+            int add = 0;
+            for (int w = 0; w < ST_WAVES; ++w) { add += cntw[w][tid]; cntw[w][tid] = 0; }
+            if (tid < e_loc) run_el[tid] += add;
+        }
+        if (mine) {
+            const int q = q_base + excl;
+            int lo = 0, hi = W;
+            while (lo < hi) {
+                int mid = (lo + hi) >> 1;
+                int cum = win_in_lds ? lds_win[mid].y : my_ws[mid].y;
+                if (cum > q) hi = mid; else lo = mid + 1;
+            }
+            const bool left = s != r && lo >= W;
+            const int slice = s == r ? 0 : (left ? kmax + 1 : (win_in_lds ? lds_win[lo].x : my_ws[lo].x));
+            const int pos = offsets[(size_t)slice * e_loc + el] + (left ? res_base[el] : 0) + before - pre[lo * e_loc + el];
+            if (row_arrival) row_arrival[pos] = src_base + q;
+            if (row_assignment) row_assignment[pos] = s * per_src + x;
+        }
+        q_base += tot;
+        __syncthreads();
     }
 }
 
@@ -161,16 +263,14 @@ size_t sizes_bytes(int kmax, int e_loc) {
     return (b + 255) & ~(size_t)255;
 }
 
-}  // namespace
-
-extern "C" size_t moe_slice_table_workspace_bytes(int N, int kmax, int E) {
-    if (N < 1 || kmax < 0 || E < 1 || E % N != 0) return 0;
-    return sizes_bytes(kmax, E / N) + (size_t)N * (kmax > 0 ? kmax : 1) * sizeof(int2);
+size_t rows_extra_bytes(int N, int kmax, int e_loc) {
+    return ((size_t)N * (kmax + 1) * e_loc + (size_t)N * e_loc + (size_t)N) * sizeof(int32_t);
 }
 
-extern "C" moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk, int E, int r, const int32_t* traffic,
-                                      const uint8_t* perms, const int32_t* durations, const int32_t* count, int kmax,
-                                      int32_t* offsets, void* workspace, size_t workspace_bytes, void* hip_stream) {
+moe_status slice_table_impl(const int32_t* ids, int N, int T, int topk, int E, int r, const int32_t* traffic,
+                            const uint8_t* perms, const int32_t* durations, const int32_t* count, int kmax,
+                            int32_t* offsets, bool want_rows, int32_t* row_arrival, int32_t* row_assignment,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (N < 1 || T < 0 || topk < 1 || E < 1 || kmax < 0 || r < 0 || r >= N) return MOE_ERR_INVALID_ARG;
     if (!traffic || !count || !offsets || (kmax > 0 && (!perms || !durations))) return MOE_ERR_INVALID_ARG;
     if (E % N != 0 || N > 256) return MOE_ERR_UNSUPPORTED_SHAPE;
@@ -180,10 +280,18 @@ extern "C" moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk
     const int e_loc = E / N;
     const long long G = (long long)(kmax + 2) * e_loc;
     if (G >= (1LL << 30)) return MOE_ERR_UNSUPPORTED_SHAPE;
-    if (!workspace || workspace_bytes < moe_slice_table_workspace_bytes(N, kmax, E)) return MOE_ERR_WORKSPACE;
+    if (want_rows && ((long long)(kmax + 1) * e_loc > CNT_CAP || e_loc > PLACE_MAX_ELOC)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    const size_t need = want_rows ? moe_slice_table_rows_workspace_bytes(N, kmax, E) : moe_slice_table_workspace_bytes(N, kmax, E);
+    if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     int32_t* sizes = (int32_t*)workspace;
     int2* win_ws = (int2*)((char*)workspace + sizes_bytes(kmax, e_loc));
+    int32_t *wcnt_ws = nullptr, *res_cnt = nullptr, *wcount = nullptr;
+    if (want_rows) {
+        wcnt_ws = (int32_t*)((char*)workspace + moe_slice_table_workspace_bytes(N, kmax, E));
+        res_cnt = wcnt_ws + (size_t)N * (kmax + 1) * e_loc;
+        wcount = res_cnt + (size_t)N * e_loc;
+    }
     {
         moe::LaunchScope k("st_zero_kernel", s);
         int blocks = (int)((G + 255) / 256);
@@ -195,11 +303,46 @@ extern "C" moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk
     {
         moe::LaunchScope k("st_count_kernel", s);
         hipLaunchKernelGGL(st_count_kernel, dim3(N), dim3(ST_THREADS), 0, s, ids, N, (int)per_src, E, e_loc, r, traffic,
-                           perms, durations, count, kmax, sizes, win_ws);
+                           perms, durations, count, kmax, sizes, win_ws, wcnt_ws, res_cnt, wcount);
         moe_status st = k.done();
         if (st != MOE_OK) return st;
     }
-    moe::LaunchScope k("st_scan_kernel", s);
-    hipLaunchKernelGGL(st_scan_kernel, dim3(1), dim3(ST_THREADS), 0, s, sizes, (int)G, offsets);
+    {
+        moe::LaunchScope k("st_scan_kernel", s);
+        hipLaunchKernelGGL(st_scan_kernel, dim3(1), dim3(ST_THREADS), 0, s, sizes, (int)G, offsets);
+        moe_status st = k.done();
+        if (st != MOE_OK || !want_rows) return st;
+    }
+    moe::LaunchScope k("st_place_kernel", s);
+    hipLaunchKernelGGL(st_place_kernel, dim3(N), dim3(ST_THREADS), 0, s, ids, N, (int)per_src, E, e_loc, r, traffic, kmax,
+                       offsets, win_ws, wcnt_ws, res_cnt, wcount, row_arrival, row_assignment);
     return k.done();
+}
+
+}  // namespace
+
+extern "C" size_t moe_slice_table_workspace_bytes(int N, int kmax, int E) {
+    if (N < 1 || kmax < 0 || E < 1 || E % N != 0) return 0;
+    return sizes_bytes(kmax, E / N) + (size_t)N * (kmax > 0 ? kmax : 1) * sizeof(int2);
+}
+
+extern "C" size_t moe_slice_table_rows_workspace_bytes(int N, int kmax, int E) {
+    const size_t base = moe_slice_table_workspace_bytes(N, kmax, E);
+    return base == 0 ? 0 : base + rows_extra_bytes(N, kmax, E / N);
+}
+
+extern "C" moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk, int E, int r, const int32_t* traffic,
+                                      const uint8_t* perms, const int32_t* durations, const int32_t* count, int kmax,
+                                      int32_t* offsets, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return slice_table_impl(ids, N, T, topk, E, r, traffic, perms, durations, count, kmax, offsets, false, nullptr, nullptr,
+                            workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" moe_status moe_slice_table_rows(const int32_t* ids, int N, int T, int topk, int E, int r, const int32_t* traffic,
+                                           const uint8_t* perms, const int32_t* durations, const int32_t* count, int kmax,
+                                           int32_t* offsets, int32_t* row_arrival, int32_t* row_assignment, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream) {
+    if (!row_arrival && !row_assignment) return MOE_ERR_INVALID_ARG;
+    return slice_table_impl(ids, N, T, topk, E, r, traffic, perms, durations, count, kmax, offsets, true, row_arrival,
+                            row_assignment, workspace, workspace_bytes, hip_stream);
 }

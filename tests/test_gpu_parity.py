@@ -240,6 +240,62 @@ def test_slice_table_many_windows(lib):
     assert np.array_equal(off.cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("name,which", [("tiny", "greedy"), ("tiny", "bvn"), ("c2", "greedy"), ("c2", "bvn"), ("c3", "greedy")])
+def test_slice_table_rows(lib, name, which):
+    """Row map: assignment index bit-exact with the oracle; the arrival index is the rank of that assignment among
+    all assignments destined to r (sources in rank order, each in arrival order)."""
+    say("slice table rows", name, which)
+    cfg = workloads.CONFIGS[name]
+    ids = workloads.config_routing(cfg)
+    traffic, _ = oracle.route_histogram(ids, cfg.E)
+    order = np.argsort(-traffic.sum(0), kind="stable")
+    kmax = cfg.kmax if which == "greedy" else oracle.bvn_bound(cfg.N)
+    d_ids, d_traffic = dev(ids), dev(traffic)
+    if which == "greedy":
+        rp, rd, _ = oracle.decompose_greedy(traffic, kmax, zero_diag=True)
+    else:
+        rp, rd, _, _, _ = oracle.decompose_bvn(traffic, kmax, zero_diag=True)
+    pp = np.zeros((kmax, cfg.N), dtype=np.uint8)
+    dd = np.zeros(kmax, dtype=np.int32)
+    pp[:len(rp)], dd[:len(rd)] = rp, rd
+    cnt = np.array([len(rp)], dtype=np.int32)
+    for r in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):
+        M = int(traffic[:, r].sum())
+        off, arr, asg = lib.moe_slice_table_rows(d_ids, cfg.E, r, d_traffic, dev(pp), dev(dd), dev(cnt), kmax, M)
+        torch.cuda.synchronize()
+        ref_off, ref_rows = oracle.slice_table(ids, cfg.E, r, traffic, rp, rd, kmax)
+        assert np.array_equal(off.cpu().numpy(), ref_off), (name, which, r)
+        assert np.array_equal(asg.cpu().numpy(), ref_rows), (name, which, r)
+        assert np.array_equal(arr.cpu().numpy(), np.searchsorted(np.sort(ref_rows), ref_rows)), (name, which, r)
+        only = lib.moe_slice_table_rows(d_ids, cfg.E, r, d_traffic, dev(pp), dev(dd), dev(cnt), kmax, M, want_assignment=False)
+        torch.cuda.synchronize()
+        assert only[2] is None and np.array_equal(only[1].cpu().numpy(), arr.cpu().numpy())
+
+
+def test_slice_table_rows_shapes_and_errors(lib):
+    say("slice table rows shapes")
+    rng = np.random.default_rng(8)
+    # many experts per rank (64), ids outside [0, E) are dropped, a schedule that ships in small pieces
+    N, E, T, topk, r = 3, 192, 700, 3, 1
+    ids = rng.integers(-5, E + 5, size=(N, T, topk)).astype(np.int32)
+    traffic, _ = oracle.route_histogram(ids, E)
+    kmax = 40
+    perms = np.tile(np.array([[1, 2, 0]], dtype=np.uint8), (kmax, 1))          # source 0 -> r
+    perms[1::2] = np.array([2, 0, 1], dtype=np.uint8)                          # every other: source 2 -> r
+    dur = rng.integers(0, 30, size=kmax).astype(np.int32)
+    M = int(traffic[:, r].sum())
+    off, arr, asg = lib.moe_slice_table_rows(dev(ids), E, r, dev(traffic), dev(perms), dev(dur), dev(np.array([kmax - 3], dtype=np.int32)), kmax, M)
+    torch.cuda.synchronize()
+    ref_off, ref_rows = oracle.slice_table(ids, E, r, traffic, perms[:kmax - 3], dur[:kmax - 3], kmax)
+    assert np.array_equal(off.cpu().numpy(), ref_off) and np.array_equal(asg.cpu().numpy(), ref_rows)
+    assert np.array_equal(np.sort(arr.cpu().numpy()), np.arange(M))
+    # too many (window, expert) counters for the row map: refused, the plain table still works
+    big_k = 8192 // 64 + 1
+    with pytest.raises(lib.MoeError):
+        lib.moe_slice_table_rows(dev(ids), E, r, dev(traffic), dev(np.zeros((big_k, N), dtype=np.uint8)),
+                                 dev(np.zeros(big_k, dtype=np.int32)), dev(np.zeros(1, dtype=np.int32)), big_k, M)
+
+
 # ------------------------------------------------------------------------------ FFN
 def ffn_error(y_gpu_bits, y_ref, offsets, rows=None):
     """max over (slice, expert) groups of max|y - yref| / max|yref| on the given rows."""
@@ -316,6 +372,88 @@ def test_ffn_edge_cases(lib):
     with pytest.raises(lib.MoeError):
         lib.moe_expert_ffn_sliced(dev_bf16(x[:, :128]), dev(off), 2, E_loc, w_gate=up["w_gate"][:, :, :128].contiguous(),
                                   w_up=up["w_up"][:, :, :128].contiguous(), w_down=up["w_down"][:, :128].contiguous())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("tile_rows", ["64", "256"])
+def test_ffn_mapped(lib, dtype, tile_rows):
+    """Gather / scatter through a row map and the router weight in the epilogue."""
+    say("ffn mapped", dtype, tile_rows)
+    os.environ["MOE_FFN_ROWS"] = tile_rows
+    try:
+        E_loc, d, f, M, S = 2, 512, 384, 1500, 4
+        rng = np.random.default_rng(77)
+        W = workloads.ffn_weights(E_loc, d, f, seed=5, dtype=dtype)
+        x = workloads.activations(M, d, seed=6)                                          # arrival order
+        offsets = workloads.random_offsets(S * E_loc, M - 40, seed=7)                    # 40 arrival rows are never scheduled
+        used = int(offsets[-1])
+        row_map = rng.permutation(M)[:used].astype(np.int32)
+        gate = rng.uniform(0.05, 1.0, size=used).astype(np.float32)
+        y0 = torch.full((M, d), 3.0, dtype=torch.bfloat16, device=DEV)
+        y = lib.moe_expert_ffn_sliced_mapped(dev_bf16(x), dev(offsets), S, E_loc, row_map=dev(row_map), row_gate=dev(gate),
+                                             y=y0, **upload_weights(W))
+        torch.cuda.synchronize()
+        ref, target = oracle.expert_ffn_sliced_mapped(x, offsets, E_loc, W, row_map, gate)
+        yb = host_bf16_bits(y)
+        err = ffn_error(yb[target], ref, offsets)
+        say("   max relative error", err)
+        assert err <= FFN_TOL[dtype]
+        untouched = np.setdiff1d(np.arange(M), target)
+        assert (oracle.decode_bf16(yb[untouched]) == 3.0).all()
+        # identity map and unit gate: the very bytes of the plain call
+        ident = np.arange(used, dtype=np.int32)
+        ya = lib.moe_expert_ffn_sliced_mapped(dev_bf16(x), dev(offsets), S, E_loc, row_map=dev(ident),
+                                              row_gate=dev(np.ones(used, dtype=np.float32)), **upload_weights(W))
+        yp = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(offsets), S, E_loc, **upload_weights(W))
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bf16_bits(ya)[:used], host_bf16_bits(yp)[:used])
+        # gathering through the map equals running the plain call on rows gathered beforehand
+        yg = lib.moe_expert_ffn_sliced(dev_bf16(np.ascontiguousarray(x[row_map])), dev(offsets), S, E_loc, **upload_weights(W))
+        ym = lib.moe_expert_ffn_sliced_mapped(dev_bf16(x), dev(offsets), S, E_loc, row_map=dev(row_map), **upload_weights(W))
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bf16_bits(ym)[row_map], host_bf16_bits(yg)[:used])
+    finally:
+        os.environ.pop("MOE_FFN_ROWS", None)
+
+
+def sample_rows(off, per_group, seed=1):
+    """Every non-empty group contributes its first and last rows plus a random sample."""
+    rng = np.random.default_rng(seed)
+    off = np.asarray(off, dtype=np.int64)
+    rows = []
+    for g in range(len(off) - 1):
+        lo, hi = off[g], off[g + 1]
+        if hi > lo:
+            rows += [lo, hi - 1] + list(rng.integers(lo, hi, size=min(per_group, hi - lo)))
+    return np.unique(np.array(rows, dtype=np.int64))
+
+
+def test_whole_path_with_row_map_c2(lib):
+    """c2 at full size: rows arrive source by source; slice table -> row map -> FFN with fused gather / scatter."""
+    say("whole path with row map, c2")
+    cfg = workloads.CONFIGS["c2"]
+    ids = workloads.config_routing(cfg)
+    d_ids = dev(ids)
+    traffic, _ = lib.moe_route_histogram(d_ids, cfg.E)
+    r = int(traffic.sum(0).argmax().item())
+    sched = lib.moe_decompose_greedy(traffic.unsqueeze(0), cfg.kmax, zero_diag=True)
+    M = int(traffic[:, r].sum().item())
+    offsets, arr, asg = lib.moe_slice_table_rows(d_ids, cfg.E, r, traffic, sched["perms"][0], sched["durations"][0],
+                                                 sched["counts"], cfg.kmax, M)
+    W = workloads.ffn_weights(cfg.E_loc, cfg.d, cfg.f, seed=cfg.seed, dtype=cfg.weight_dtype)
+    x = workloads.activations(M, cfg.d, seed=cfg.seed + 1)                                # arrival order
+    y = lib.moe_expert_ffn_sliced_mapped(dev_bf16(x), offsets, cfg.kmax + 2, cfg.E_loc, row_map=arr, **upload_weights(W))
+    torch.cuda.synchronize()
+    th = traffic.cpu().numpy()
+    rp, rd, _ = oracle.decompose_greedy(th, cfg.kmax, zero_diag=True)
+    ref_off, ref_rows = oracle.slice_table(ids, cfg.E, r, th, rp, rd, cfg.kmax)
+    assert np.array_equal(offsets.cpu().numpy(), ref_off) and np.array_equal(asg.cpu().numpy(), ref_rows)
+    row_map = np.searchsorted(np.sort(ref_rows), ref_rows)
+    rows = sample_rows(ref_off, per_group=6)
+    ref, target = oracle.expert_ffn_sliced_mapped(x, ref_off, cfg.E_loc, W, row_map, rows=rows)
+    err = ffn_error(host_bf16_bits(y)[target], ref, ref_off, rows=rows)
+    say("   max relative error on", len(rows), "sampled rows:", err)
+    assert err <= FFN_TOL["bf16"]
 
 
 # ------------------------------------------------------------------------------ whole path, full-size configs
