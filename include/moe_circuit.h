@@ -260,6 +260,10 @@ moe_status moe_order_matchings(const int32_t* traffic, int N, const uint8_t* per
  * Not thread safe; intended for single-threaded benchmarks.
  * ------------------------------------------------------------------------------------------- */
 moe_status moe_kernel_timing_enable(int on);
+/* Restrict the timing to one kernel name (as reported by moe_kernel_timing_read, e.g. "ffn_gemm1_kernel"; host
+ * string, copied): an event pair costs a few microseconds of stream time, which matters when a whole step of
+ * small kernels is being measured at the same time.  NULL = every kernel (the default). */
+moe_status moe_kernel_timing_select(const char* kernel_name);
 int        moe_kernel_timing_read(const char** names, float* total_ms, int* launches, int cap);
 
 /* Text of the last HIP error seen by this library in the calling process (host pointer). */

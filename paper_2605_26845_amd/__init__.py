@@ -27,7 +27,7 @@ _STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAP
 EXPORTS = [
     "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
-    "moe_kernel_timing_read", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
+    "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped",
 ]
 
@@ -100,6 +100,8 @@ def load():
     L.moe_expert_ffn_sliced.restype = ci
     L.moe_kernel_timing_enable.argtypes = [ci]
     L.moe_kernel_timing_enable.restype = ci
+    L.moe_kernel_timing_select.argtypes = [ctypes.c_char_p]
+    L.moe_kernel_timing_select.restype = ci
     L.moe_kernel_timing_read.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
                                          ctypes.POINTER(ctypes.c_int), ci]
     L.moe_kernel_timing_read.restype = ci
@@ -325,6 +327,11 @@ def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, 
 
 def moe_kernel_timing_enable(on: bool):
     _check(load().moe_kernel_timing_enable(1 if on else 0), "moe_kernel_timing_enable")
+
+
+def moe_kernel_timing_select(kernel_name=None):
+    """Time only the launches of one kernel (None = all)."""
+    _check(load().moe_kernel_timing_select(None if kernel_name is None else kernel_name.encode()), "moe_kernel_timing_select")
 
 
 def moe_kernel_timing_read(cap: int = 32):

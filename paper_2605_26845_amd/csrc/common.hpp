@@ -10,6 +10,7 @@ namespace moe {
 
 void        note_hip_error(hipError_t e, const char* what);
 bool        timing_enabled();
+bool        timing_wanted(const char* kernel_name);      // timing on, and this kernel selected
 void        timing_begin(const char* name, hipStream_t s);
 void        timing_end(hipStream_t s);
 
@@ -17,10 +18,11 @@ void        timing_end(hipStream_t s);
 // into MOE_ERR_HIP.
 struct LaunchScope {
     hipStream_t s;
-    LaunchScope(const char* name, hipStream_t stream) : s(stream) { if (timing_enabled()) timing_begin(name, s); }
+    bool timed;
+    LaunchScope(const char* name, hipStream_t stream) : s(stream), timed(timing_wanted(name)) { if (timed) timing_begin(name, s); }
     moe_status done() {
         hipError_t e = hipGetLastError();
-        if (timing_enabled()) timing_end(s);
+        if (timed) timing_end(s);
         if (e != hipSuccess) { note_hip_error(e, "kernel launch"); return MOE_ERR_HIP; }
         return MOE_OK;
     }

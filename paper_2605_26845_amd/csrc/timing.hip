@@ -8,6 +8,7 @@ namespace moe {
 
 static char g_err[256] = "";
 static bool g_timing = false;
+static char g_only[64] = "";      // when not empty: the one kernel whose launches are timed
 
 struct Span { const char* name; hipEvent_t a, b; };
 static std::vector<Span> g_spans;
@@ -18,6 +19,7 @@ void note_hip_error(hipError_t e, const char* what) {
     snprintf(g_err, sizeof(g_err), "%s: %s", what, hipGetErrorString(e));
 }
 bool timing_enabled() { return g_timing; }
+bool timing_wanted(const char* kernel_name) { return g_timing && (g_only[0] == 0 || strcmp(g_only, kernel_name) == 0); }
 
 static hipEvent_t get_event() {
     if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
@@ -41,6 +43,12 @@ void timing_end(hipStream_t s) {
 
 extern "C" moe_status moe_kernel_timing_enable(int on) {
     moe::g_timing = on != 0;
+    return MOE_OK;
+}
+
+extern "C" moe_status moe_kernel_timing_select(const char* kernel_name) {
+    if (kernel_name && strlen(kernel_name) >= sizeof(moe::g_only)) return MOE_ERR_INVALID_ARG;
+    if (kernel_name) strcpy(moe::g_only, kernel_name); else moe::g_only[0] = 0;
     return MOE_OK;
 }
 
