@@ -32,11 +32,76 @@ def parse():
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (reference reading for HBM byte counters)")
+    ap.add_argument("--summarize-counters", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: turn the counter_collection.csv files of the two rocprofv3 --pmc runs (FETCH_SIZE, "
+                         "WRITE_SIZE; both with --calibration-copy) into profiles/ffn_<workload>_hbm_traffic.{md,json}")
     return ap.parse_args()
+
+
+def summarize_counters(workload, fetch_csv, write_csv):
+    """FETCH_SIZE / WRITE_SIZE (KiB per dispatch) of the two FFN kernels, scaled by what the same counter reads for the
+    256 MiB calibration copy; stored with the SHA-256 of the kernel source it was measured on."""
+    import collections
+    import csv
+    import hashlib
+
+    def averages(path):
+        acc = collections.defaultdict(list)
+        for row in csv.DictReader(open(path)):
+            k = row["Kernel_Name"]
+            key = ("ffn_gemm1_kernel" if "ffn_adaptive_kernel<1>" in k or "ffn_gemm_kernel<1," in k else
+                   "ffn_gemm2_kernel" if "ffn_adaptive_kernel<2>" in k or "ffn_gemm_kernel<2," in k else
+                   "copy" if "copyBuffer" in k else None)
+            if key:
+                acc[key].append(float(row["Counter_Value"]))
+        return {k: (max(v) if k == "copy" else sum(v) / len(v)) for k, v in acc.items()}     # the copy: its largest dispatch
+
+    f, w = averages(fetch_csv), averages(write_csv)
+    cal_f, cal_w = 262144.0 / f["copy"], 262144.0 / w["copy"]
+    detail = {}
+    for k in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
+        rb, wb = f[k] * cal_f * 1024, w[k] * cal_w * 1024
+        detail[k] = {"read_bytes": rb, "write_bytes": wb, "total_bytes": rb + wb}
+    rel = "paper_2605_26845_amd/csrc/ffn.hip"
+    sha = hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest()
+    base = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic" % workload)
+    json.dump({"kernel": "ffn_gemm1_kernel", "workload": workload, "source_sha256": {rel: sha},
+               "traffic_bytes_per_launch": detail["ffn_gemm1_kernel"]["total_bytes"], "detail": detail,
+               "see": "profiles/ffn_%s_hbm_traffic.md" % workload}, open(base + ".json", "w"), indent=1)
+    lines = ["# HBM-side byte counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels (gemm1 = phase 1: gate/up + SwiGLU)" % workload,
+             "", "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box, one counter per run; then the summary, no GPU needed):", ""]
+    for c in ("FETCH_SIZE", "WRITE_SIZE"):
+        lines.append("    rocprofv3 --pmc %s --output-format csv -d gpurun_out/pmc_%s -o p -- python3 bench.py --workload %s --steps 10 "
+                     "--warmup 2 --no-extras --no-cpu-baseline --calibration-copy" % (c, c, workload))
+    lines += ["    python3 bench.py --workload %s --summarize-counters gpurun_out/pmc_FETCH_SIZE/p_counter_collection.csv "
+              "gpurun_out/pmc_WRITE_SIZE/p_counter_collection.csv" % workload, "",
+              "Calibration: the plain device-to-device copy of 256 MiB (`--calibration-copy`, the largest __amd_rocclr_copyBuffer dispatch) reads",
+              "FETCH_SIZE = %.1f and WRITE_SIZE = %.1f for 262144 KiB each way -> scale factors %.4f (fetch) and %.4f (write)."
+              % (f["copy"], w["copy"], cal_f, cal_w), "",
+              "| kernel | FETCH_SIZE avg | WRITE_SIZE avg | scaled read MB | scaled write MB | total MB per launch |", "|---|---|---|---|---|---|"]
+    for k in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
+        d = detail[k]
+        lines.append("| %s | %.0f | %.0f | %.1f | %.1f | %.1f |" % (k, f[k], w[k], d["read_bytes"] / 1e6, d["write_bytes"] / 1e6, d["total_bytes"] / 1e6))
+    import numpy as np
+    import workloads
+    cfg = workloads.CONFIGS[workload]
+    dest = workloads.config_routing(cfg) // cfg.E_loc
+    M = int(np.bincount(dest.ravel(), minlength=cfg.N).max())                  # rows of the hottest receiving rank
+    xb, wb_, hb = M * cfg.d * 2, 2 * cfg.E_loc * cfg.d * cfg.f * 2, M * cfg.f * 2
+    lines += ["", "Algorithmic bytes of ffn_gemm1_kernel at this workload (M=%d, d=%d, f=%d, %d experts): x %.1f MB + gate/up weights %.1f MB read,"
+              % (M, cfg.d, cfg.f, cfg.E_loc, xb / 1e6, wb_ / 1e6),
+              "h %.1f MB written = %.1f MB." % (hb / 1e6, (xb + wb_ + hb) / 1e6)]
+    lines += ["The fetch counter sits between the L2 and the fabric: it also counts reads served by the 256 MB memory-side cache.",
+              "The stored figure (`.json`) carries the SHA-256 of ffn.hip it was measured on; bench.py reports it as `roofline.traffic` only while that matches.", ""]
+    open(base + ".md", "w").write("\n".join(lines))
+    print(base + ".md")
 
 
 def main():
     args = parse()
+    if args.summarize_counters:
+        summarize_counters(args.workload, *args.summarize_counters)
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
