@@ -275,6 +275,14 @@ def extras(moe, torch, np, workloads, dev):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     out["greedy_128x128_k32"] = {"matrices": B, "matrices_per_s": B / dt, "matchings_per_s": float(bufs["counts"].sum().item()) / dt}
+    # the same batch with the residual held in 16 bits (its entries are below 65536): twice the matrices in flight per CU
+    moe.moe_decompose_greedy(mats, 32, zero_diag=True, out=bufs, entries_u16=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    moe.moe_decompose_greedy(mats, 32, zero_diag=True, out=bufs, entries_u16=True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    out["greedy_128x128_k32_u16"] = {"matrices": B, "matrices_per_s": B / dt, "matchings_per_s": float(bufs["counts"].sum().item()) / dt}
     Bb = 256
     bb = dict(perms=None, durations=None, counts=torch.zeros((Bb,), dtype=torch.int32, device=dev), residual=None,
               hashes=None, pad_total=torch.zeros((Bb,), dtype=torch.int32, device=dev))

@@ -38,6 +38,9 @@ typedef int moe_status;
 
 /* flags of the decomposition calls */
 #define MOE_DECOMP_ZERO_DIAGONAL 1  /* treat the diagonal (tokens whose expert is local) as zero */
+#define MOE_DECOMP_ENTRIES_U16   2  /* moe_decompose_greedy only: the caller vouches that every entry is < 65536; the
+                                       residual is then kept in 16 bits (half the on-chip memory per matrix, twice
+                                       the matrices in flight).  A matrix with a larger entry gets counts[b] = -1. */
 
 /* weight formats of moe_expert_ffn_sliced */
 #define MOE_W_BF16            0   /* bfloat16                                                     */

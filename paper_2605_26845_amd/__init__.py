@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libmoecircuit.so")
 _INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 
 MOE_DECOMP_ZERO_DIAGONAL = 1
+MOE_DECOMP_ENTRIES_U16 = 2
 MOE_W_BF16 = 0
 MOE_W_FP8_E4M3_B128 = 1
 MOE_MAX_RANKS = 128
@@ -179,13 +180,15 @@ def _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out):
 
 
 def moe_decompose_greedy(mats, kmax: int, zero_diag: bool = False, want_perms=True, want_residual=True,
-                         want_hashes=False, out=None):
-    """mats int32 [B][N][N] -> dict(perms, durations, counts, residual, hashes) of device tensors."""
+                         want_hashes=False, out=None, entries_u16: bool = False):
+    """mats int32 [B][N][N] -> dict(perms, durations, counts, residual, hashes) of device tensors.
+    entries_u16: the caller vouches for entries < 65536 (16-bit residual on chip; counts[b] = -1 where that is false)."""
     import torch
     _dev_check(mats, torch.int32, "mats")
     B, N, _ = mats.shape
     o = _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out)
-    _check(load().moe_decompose_greedy(_ptr(mats), B, N, kmax, MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0,
+    _check(load().moe_decompose_greedy(_ptr(mats), B, N, kmax,
+                                       (MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0) | (MOE_DECOMP_ENTRIES_U16 if entries_u16 else 0),
                                        _ptr(o["perms"]), _ptr(o["durations"]), _ptr(o["counts"]), _ptr(o["residual"]),
                                        _ptr(o["hashes"]), _stream()), "moe_decompose_greedy")
     return o

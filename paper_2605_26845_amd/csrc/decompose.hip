@@ -136,7 +136,23 @@ __device__ __forceinline__ Mask<NPL> bcast_mask(const Mask<NPL> (&m)[NPL], int r
 
 // ------------------------------------------------------------------------------ shared pieces
 // Copy one matrix into LDS (optionally with the diagonal forced to zero).
-__device__ __forceinline__ void load_matrix(const int32_t* __restrict__ A, int32_t* R, int N, bool zero_diag, int lane) {
+// 16-bit residual (the caller vouches for entries below 65536): returns false if an entry does not fit.
+__device__ __forceinline__ bool load_matrix(const int32_t* __restrict__ A, uint16_t* R, int N, bool zero_diag, int lane) {
+    const int total = N * N;
+    bool ok = true;
+    for (int x = lane; x < total; x += MOE_WAVE) {
+        const int v = A[x];
+        ok = ok && (unsigned)v < 65536u;
+        R[x] = (uint16_t)v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (zero_diag) {
+        for (int i = lane; i < N; i += MOE_WAVE) R[i * N + i] = 0;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+    return __ballot(!ok) == 0;
+}
+__device__ __forceinline__ bool load_matrix(const int32_t* __restrict__ A, int32_t* R, int N, bool zero_diag, int lane) {
     const int total = N * N;
     if ((total & 3) == 0 && (((uintptr_t)A) & 15) == 0) {
         const int4* src = reinterpret_cast<const int4*>(A);
@@ -150,8 +166,10 @@ __device__ __forceinline__ void load_matrix(const int32_t* __restrict__ A, int32
         for (int i = lane; i < N; i += MOE_WAVE) R[i * N + i] = 0;
         lds_fence();
     }
+    return true;
 }
-__device__ __forceinline__ void store_matrix(const int32_t* R, int32_t* __restrict__ out, int N, int lane) {
+template <typename T>
+__device__ __forceinline__ void store_matrix(const T* R, int32_t* __restrict__ out, int N, int lane) {
     const int total = N * N;
     for (int x = lane; x < total; x += MOE_WAVE) out[x] = R[x];
 }
@@ -344,15 +362,19 @@ __device__ __forceinline__ void emit_matching(const int (&sigma)[NPL], int durat
 }
 
 // ------------------------------------------------------------------------------ greedy kernel
-template <int NPL>
+template <int NPL, typename T>
 __global__ __launch_bounds__(MOE_WAVE)
 void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
                    int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
                    unsigned long long* __restrict__ hashes) {
-    extern __shared__ int32_t R[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char greedy_lds[];
+    T* R = reinterpret_cast<T*>(greedy_lds);           // T = uint16_t halves the footprint: twice the wavefronts per CU
     const int lane = threadIdx.x;
     const int b = blockIdx.x;
-    load_matrix(mats + (size_t)b * N * N, R, N, flags & MOE_DECOMP_ZERO_DIAGONAL, lane);
+    if (!load_matrix(mats + (size_t)b * N * N, R, N, flags & MOE_DECOMP_ZERO_DIAGONAL, lane)) {
+        if (lane == 0) { counts[b] = -1; if (hashes) hashes[b] = 0; }      // an entry does not fit 16 bits
+        return;
+    }
 
     // feasible start: u_i = row maximum, v_j = 0  (u_i + v_j >= R_ij)
     int u[NPL], v[NPL], p[NPL], sigma[NPL];
@@ -414,7 +436,7 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                 for (int s = 0; s < NPL; ++s)
                     if (lane == (i0 & 63) && s == (i0 >> 6)) intree[s] = true;
                 const int ui0 = bcast<NPL>(u, i0);
-                const int32_t* row = R + i0 * N;
+                const T* row = R + i0 * N;
                 int local = INT_MAX;
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) {
@@ -463,7 +485,7 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             int vv[NPL];
 #pragma unroll
             for (int s = 0; s < NPL; ++s) vv[s] = v[s];
-            build_masks<NPL, int32_t>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
+            build_masks<NPL, T>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
         }
         lex_smallest<NPL>(tm, N, lane, sigma, p, 0);
         // ---- ship whole entries; the matching lasts as long as its heaviest pair
@@ -877,14 +899,13 @@ extern "C" moe_status moe_decompose_greedy(const int32_t* mats, int B, int N, in
     if (st != MOE_OK) return st;
     if (B == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)hip_stream;
-    const size_t lds = (size_t)N * N * sizeof(int32_t);
+    const bool narrow = (flags & MOE_DECOMP_ENTRIES_U16) != 0;
+    const size_t lds = (size_t)N * N * (narrow ? sizeof(uint16_t) : sizeof(int32_t));
     moe::LaunchScope k("greedy_kernel", s);
-    if (N <= 64)
-        hipLaunchKernelGGL(greedy_kernel<1>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations,
-                           counts, residual, (unsigned long long*)hashes);
-    else
-        hipLaunchKernelGGL(greedy_kernel<2>, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations,
-                           counts, residual, (unsigned long long*)hashes);
+    auto kern = N <= 64 ? (narrow ? greedy_kernel<1, uint16_t> : greedy_kernel<1, int32_t>)
+                        : (narrow ? greedy_kernel<2, uint16_t> : greedy_kernel<2, int32_t>);
+    hipLaunchKernelGGL(kern, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts, residual,
+                       (unsigned long long*)hashes);
     return k.done();
 }
 

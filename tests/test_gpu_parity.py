@@ -142,6 +142,34 @@ def test_decompose_special_cases(lib):
         lib.moe_decompose_greedy(torch.zeros((1, 129, 129), dtype=torch.int32, device=DEV), 4)
 
 
+def test_greedy_16_bit_residual(lib):
+    """Same bytes as the 32-bit residual when every entry is below 65536; a larger entry is reported, not truncated."""
+    say("greedy 16-bit residual")
+    for N, kmax in ((5, 12), (16, 8), (64, 70), (128, 32)):
+        mats = workloads.random_matrices(4, N, seed=70 + N, density=0.8, high=65536)
+        mats[0, 0, 1 % N] = 65535
+        a = lib.moe_decompose_greedy(dev(mats), kmax, zero_diag=True, want_hashes=True)
+        b = lib.moe_decompose_greedy(dev(mats), kmax, zero_diag=True, want_hashes=True, entries_u16=True)
+        torch.cuda.synchronize()
+        for key in ("perms", "durations", "counts", "residual", "hashes"):
+            assert torch.equal(a[key], b[key]), (N, key)
+        ref = oracle.decompose_batch("greedy", mats, kmax, zero_diag=True)
+        assert np.array_equal(b["hashes"].cpu().numpy().view(np.uint64), ref["hashes"])
+    stress = workloads.stress_matrices(16, 128)
+    assert stress.max() < 65536
+    b = lib.moe_decompose_greedy(dev(stress), 32, zero_diag=True, want_hashes=True, entries_u16=True)
+    torch.cuda.synchronize()
+    ref = oracle.decompose_batch("greedy", stress, 32, zero_diag=True, nthreads=8)
+    assert np.array_equal(b["hashes"].cpu().numpy().view(np.uint64), ref["hashes"])
+    assert np.array_equal(b["residual"].cpu().numpy(), ref["residual"])
+    bad = workloads.random_matrices(3, 16, seed=5, high=1000)
+    bad[1, 3, 4] = 65536
+    o = lib.moe_decompose_greedy(dev(bad), 8, entries_u16=True)
+    torch.cuda.synchronize()
+    c = o["counts"].cpu().numpy()
+    assert c[1] == -1 and c[0] > 0 and c[2] > 0
+
+
 def test_decompose_stress_matrices_128(lib):
     """The batched stress workload at its real shape (128 x 128, Zipf rows), a sample of matrices."""
     say("decompose stress 128")
