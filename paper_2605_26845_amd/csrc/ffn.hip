@@ -88,7 +88,9 @@ void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int 
 }
 
 // ---------------------------------------------------------------------------------- helpers
-__device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+// g * sigmoid(g) with the hardware reciprocal (1 ulp) instead of an IEEE division: the result is rounded to bf16 anyway,
+// and the division's dozen instructions per value were a visible part of a tile's read-out
+__device__ __forceinline__ float silu(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
     bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
@@ -498,12 +500,14 @@ template <int CLS> struct Cls {
     static_assert(S0 + S1 + S2 == NCOPY && (S2 == 0 || SUB > 2) && (S1 == 0 || SUB > 1), "the slots hold every copy and end before the next slab's last K step");
 };
 constexpr int ADAPTIVE_LDS = 139264;                          // 2 x 68 KiB (class 2) >= 2 x 64 KiB, 3 x 40 KiB
+constexpr int STAGE_OFF = 69632;                              // output staging (8 wavefronts x 8 KiB) sits above any class's slab 0
+static_assert(STAGE_OFF + 8 * 8192 <= ADAPTIVE_LDS, "staging area inside the allocation");
 
 template <int PHASE>
 __global__ __launch_bounds__(512, 1)
 void ffn_adaptive_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ int s_ticket[3];                        // (block, tile index, class) of the next tile; block -1 = none
+    __shared__ int s_ticket[6];                        // next tile: (block, tile index, class, first row, end row, expert); block -1 = none
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -532,10 +536,12 @@ void ffn_adaptive_kernel(FfnArgs a) {
     // the unit is the first of the tile its block's class makes of it.
     auto fetch = [&](int first_k) __attribute__((always_inline)) {
         int q = my_xcd, k = first_k, blk = -1, unit = -1, cls = 0;
+        int4 info = make_int4(0, 0, 0, 0);
         for (int tries = 0; tries < 8;) {
             int st = geom.decode(q, k, blk, unit);
             if (st == 1) {
-                cls = a.plan[PLAN_HDR + blk].w;
+                info = a.plan[PLAN_HDR + blk];
+                cls = info.w;
                 if ((unit & ((1 << cls) - 1)) == 0) break;
             }
             if (st < 0) { ++tries; q = (q + 1) & 7; }
@@ -543,6 +549,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
             if (tries < 8) k = atomicAdd(&queues[q], 1);
         }
         s_ticket[0] = blk; s_ticket[1] = blk >= 0 ? (unit >> cls) : 0; s_ticket[2] = cls;
+        s_ticket[3] = info.x; s_ticket[4] = info.y; s_ticket[5] = info.z;      // the plan entry travels with the ticket
     };
     if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));
     __syncthreads();
@@ -557,17 +564,16 @@ void ffn_adaptive_kernel(FfnArgs a) {
     // unrolled copy code would keep them in memory.)
     unsigned long long wB = 0, wB_up = 0;
     unsigned int b_voff = 0;
+    bool counted_stores = false;                       // the previous tile's output went out as a known number of stores
     int m0 = 0, m_end = 0, nt = 0;
     unsigned int a_voff[4];
     unsigned int b_soff[8];
 
-    auto setup = [&](auto tag, int blk_, int nt_) __attribute__((always_inline)) {
+    auto setup = [&](auto tag, int nt_) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
-        const int blk = __builtin_amdgcn_readfirstlane(blk_);
         nt = __builtin_amdgcn_readfirstlane(nt_);
-        const int4 info = a.plan[PLAN_HDR + blk];
-        m0 = __builtin_amdgcn_readfirstlane(info.x); m_end = __builtin_amdgcn_readfirstlane(info.y);
-        const int e = __builtin_amdgcn_readfirstlane(info.z);
+        m0 = __builtin_amdgcn_readfirstlane(s_ticket[3]); m_end = __builtin_amdgcn_readfirstlane(s_ticket[4]);
+        const int e = __builtin_amdgcn_readfirstlane(s_ticket[5]);
         const int rows = min(C::BMc, m_end - m0);
         const int row0 = C::ROWB == 128 ? row0_128 : row0_64, kcg = C::ROWB == 128 ? kcg_128 : kcg_64;
 #pragma unroll
@@ -611,20 +617,22 @@ void ffn_adaptive_kernel(FfnArgs a) {
                                                      b_voff, b_soff[j] + koff, 0, 0);
         }
     };
-    auto prologue = [&](auto tag, int K_) __attribute__((always_inline)) {
+    // slabs [first, last) of the tile go out at once (the tile's opening; later slabs are spaced between the MFMAs)
+    auto prologue = [&](auto tag, int first, int last) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
-        const int NS = K_ / (C::ROWB / 2);
+        const int NS = K / (C::ROWB / 2);
 #pragma unroll
         for (int s = 0; s < C::NSS; ++s)
-            if (s < NS) {
+            if (s >= first && s < last && s < NS) {
 #pragma unroll
                 for (int n = 0; n < C::NCOPY; ++n) issue_copy(tag, s, s, n);
             }
     };
-    auto start_tile = [&](int blk, int nt_, int cls) __attribute__((always_inline)) {
-        if (cls == 0)      { setup(std::integral_constant<int, 0>{}, blk, nt_); prologue(std::integral_constant<int, 0>{}, K); }
-        else if (cls == 1) { setup(std::integral_constant<int, 1>{}, blk, nt_); prologue(std::integral_constant<int, 1>{}, K); }
-        else               { setup(std::integral_constant<int, 2>{}, blk, nt_); prologue(std::integral_constant<int, 2>{}, K); }
+    // Addresses of the tile and its slab 0 (buffer 0).  The other buffers may still stage the previous tile's output.
+    auto start_tile = [&](int nt_, int cls) __attribute__((always_inline)) {
+        if (cls == 0)      { setup(std::integral_constant<int, 0>{}, nt_); prologue(std::integral_constant<int, 0>{}, 0, 1); }
+        else if (cls == 1) { setup(std::integral_constant<int, 1>{}, nt_); prologue(std::integral_constant<int, 1>{}, 0, 1); }
+        else               { setup(std::integral_constant<int, 2>{}, nt_); prologue(std::integral_constant<int, 2>{}, 0, 1); }
     };
 
     // One tile of the class given by `tag`; its first NSS slabs are in flight.  Returns the class of the next tile
@@ -634,7 +642,8 @@ void ffn_adaptive_kernel(FfnArgs a) {
         constexpr int MB = C::MB, NQ = C::NQ, NSS = C::NSS, SUB = C::SUB;
         constexpr int ROWB = C::ROWB, NMF = MB * NQ, NR = MB + NQ;
         constexpr int LPS = C::NCOPY - (C::A_HALF ? 1 : 0);             // copies every wavefront issues per slab
-        static_assert(NSS * C::NCOPY < 64 && NSS * C::SLAB <= ADAPTIVE_LDS, "pipeline shape");
+        constexpr int NSTORE = MB * (PHASE == 1 ? 4 : 8);               // 1 KiB stores per wavefront and tile
+        static_assert(NSS * C::NCOPY < 64 && NSS * C::SLAB <= ADAPTIVE_LDS && C::SLAB <= STAGE_OFF, "pipeline shape");
         const int NS = K / (ROWB / 2);
         const int wm = wave / C::WNW, wn = wave % C::WNW;
         const int b_wave_row = PHASE == 1 ? (wn >> 1) * 256 + (wn & 1) * 64 : wn * 128;
@@ -659,8 +668,11 @@ void ffn_adaptive_kernel(FfnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
 
-        wait_slabs(min(NSS - 1, NS - 1));
-        lds_barrier();                   // slab 0 is in LDS; everybody has read this tile's ticket
+        // slab 0 went out before the previous tile's output stores, whose completion need not be awaited when their
+        // number is known (memory operations of a wavefront are counted in order)
+        if (counted_stores) wait_vmcnt<NSTORE>(); else wait_vmcnt<0>();
+        lds_barrier();                   // slab 0 is in LDS; nobody reads the output staging area or this tile's ticket any more
+        prologue(tag, 1, NSS);
         if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));             // ticket of the next tile
         bf16x8 wf[2][NQ], xf[2][MB];
 #pragma unroll
@@ -728,46 +740,89 @@ void ffn_adaptive_kernel(FfnArgs a) {
         const int em0 = m0, em_end = m_end, ent = nt;
         const int nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]), nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]),
                   ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);    // uniform: keeps the copy descriptors in scalar registers
-        if (nblk >= 0) start_tile(nblk, nnt, ncls);                     // the next tile's first slabs fly during the epilogue
+        if (nblk >= 0) start_tile(nnt, ncls);                           // the next tile's first slab flies during the epilogue
 
-        // ---- epilogue.  acc[mb][q][v]: row l31 of row block mb; column 8*(v>>2) + 4*lhi + (v&3) of column block q
+        // ---- epilogue.  acc[mb][q][v]: row l31 of row block mb; column 8*(v>>2) + 4*lhi + (v&3) of column block q.
+        // A lane holds 4 consecutive columns of one row: stored from there, one instruction would touch 32 rows with
+        // 16 bytes each, and the L2 takes one request per piece.  Each wavefront instead passes its 32-row block through
+        // a private staging area in LDS (above slab 0 of the next tile, which is arriving) and stores whole 128-byte
+        // lines: 16-byte chunk c of row r sits at position c ^ swz(r), conflict-free both ways.
         const int ug = ent * C::U + (wn >> 1);
-        if (ug < NU) {
+        constexpr int SROW = PHASE == 1 ? 128 : 256;                       // staged bytes per row: 64 / 128 columns
+        constexpr int CPR = SROW / 16;                                      // chunks per row
+        constexpr int RPI = 64 / CPR;                                       // rows one store instruction covers
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));                                    // address arithmetic stays here, not in registers held across the tile loop
+        const int el31 = lane_e & 31, elhi = lane_e >> 5;
+        const int sr = lane_e / CPR, sc = lane_e % CPR;
+        auto swz = [](int r) { return PHASE == 1 ? (r >> 1) & 7 : r & 15; };
+        unsigned char* stage = smem + STAGE_OFF + wave * (32 * SROW);
+        unsigned char* wr = stage + el31 * SROW + elhi * 8;
+        const int wrow = em0 + wm * 32 * MB;                                // first row of this wavefront
+        const bool scatter = PHASE == 2 && (a.row_map || a.row_gate);
+        // plain case: rows and columns past the end fall outside the buffer descriptor and are dropped, so every
+        // wavefront issues exactly NSTORE stores per tile
+        const int rowb = (PHASE == 1 ? a.f : a.d) * 2;
+        __bf16* obase = (PHASE == 1 ? a.h + (long long)wrow * a.f + ug * 128 + (wn & 1) * 64
+                                    : a.y + (long long)wrow * a.d + ug * 256 + (wn & 1) * 128);
+        const int live = ug < NU ? min(max(em_end - wrow, 0), 32 * MB) : 0;
+        const unsigned long long ob = (unsigned long long)obase;          // (made uniform explicitly: the descriptor must sit in scalar registers)
+        const unsigned int ob_lo = (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)ob);       // (the builtin returns int:
+        const unsigned int ob_hi = (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)(ob >> 32)); //  widen as unsigned)
+        const unsigned long long ob_u = ((unsigned long long)ob_hi << 32) | ob_lo;
+        const __amdgpu_buffer_rsrc_t rsO =
+            __builtin_amdgcn_make_buffer_rsrc((void*)ob_u, 0, __builtin_amdgcn_readfirstlane(live * rowb), 0x00020000);
+        counted_stores = !scatter;
+        if (!scatter || ug < NU) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                const int m = em0 + wm * 32 * MB + mb * 32 + l31;
-                if (m < em_end) {
-                    if (PHASE == 1) {
-                        __bf16* out = a.h + (long long)m * a.f + ug * 128 + (wn & 1) * 64 + 4 * lhi;
+                if (PHASE == 1) {
 #pragma unroll
-                        for (int q = 0; q < 2; ++q)
+                    for (int q = 0; q < 2; ++q)
 #pragma unroll
-                            for (int vg = 0; vg < 4; ++vg) {
-                                float hv[4];
+                        for (int vg = 0; vg < 4; ++vg) {
+                            float hv[4];
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) hv[j] = silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j];
-                                *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) = pack4(hv[0], hv[1], hv[2], hv[3]);
-                            }
-                    } else {
-                        __bf16* out = a.y + (long long)mapped_row(a, m) * a.d + ug * 256 + (wn & 1) * 128 + 4 * lhi;
-                        const float gate = a.row_gate ? a.row_gate[m] : 1.0f;
+                            for (int j = 0; j < 4; ++j) hv[j] = silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j];
+                            *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) = pack4(hv[0], hv[1], hv[2], hv[3]);
+                        }
+                } else {
+                    float gate = 1.0f;
+                    if (scatter && a.row_gate && wrow + mb * 32 + el31 < em_end) gate = a.row_gate[wrow + mb * 32 + el31];
 #pragma unroll
-                        for (int q = 0; q < NQ; ++q)
+                    for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                            for (int vg = 0; vg < 4; ++vg)
-                                *reinterpret_cast<u32x2*>(out + q * 32 + vg * 8) =
-                                    pack4(gate * acc[mb][q][vg * 4], gate * acc[mb][q][vg * 4 + 1], gate * acc[mb][q][vg * 4 + 2],
-                                          gate * acc[mb][q][vg * 4 + 3]);
+                        for (int vg = 0; vg < 4; ++vg)
+                            *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) =
+                                pack4(gate * acc[mb][q][vg * 4], gate * acc[mb][q][vg * 4 + 1], gate * acc[mb][q][vg * 4 + 2],
+                                      gate * acc[mb][q][vg * 4 + 3]);
+                }
+                u32x4 v[32 / RPI];
+#pragma unroll
+                for (int i = 0; i < 32 / RPI; ++i) {
+                    const int r = i * RPI + sr;
+                    v[i] = *reinterpret_cast<const u32x4*>(stage + r * SROW + ((sc ^ swz(r)) << 4));
+                }
+                if (!scatter) {
+#pragma unroll
+                    for (int i = 0; i < 32 / RPI; ++i)
+                        __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO, (mb * 32 + i * RPI + sr) * rowb + sc * 16, 0, 0);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 32 / RPI; ++i) {
+                        const int m = wrow + mb * 32 + i * RPI + sr;
+                        if (m < em_end)
+                            *reinterpret_cast<u32x4*>(a.y + (long long)mapped_row(a, m) * a.d + ug * 256 + (wn & 1) * 128 + sc * 8) = v[i];
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
             }
         }
         return nblk >= 0 ? ncls : -1;
     };
 
     int cls = __builtin_amdgcn_readfirstlane(s_ticket[2]);
-    start_tile(__builtin_amdgcn_readfirstlane(s_ticket[0]), __builtin_amdgcn_readfirstlane(s_ticket[1]), cls);
+    start_tile(__builtin_amdgcn_readfirstlane(s_ticket[1]), cls);
     while (cls >= 0) {
         if (cls == 0)      cls = run_tile(std::integral_constant<int, 0>{});
         else if (cls == 1) cls = run_tile(std::integral_constant<int, 1>{});
