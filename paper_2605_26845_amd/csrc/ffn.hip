@@ -667,6 +667,9 @@ void ffn_adaptive_kernel(FfnArgs a) {
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
+        const int em0 = m0, em_end = m_end, ent = nt;                   // this tile's rows and column unit, for the read-out
+        int nblk = -1, nnt = 0, ncls = 0;                                // ticket of the next tile
+        bool chained = false;                                            // the next tile's slab 0 was issued inside this tile
 
         // slab 0 went out before the previous tile's output stores, whose completion need not be awaited when their
         // number is known (memory operations of a wavefront are counted in order)
@@ -680,8 +683,13 @@ void ffn_adaptive_kernel(FfnArgs a) {
 
         // Slab s in buffer buf.  NEW: slab s + NSS exists (its slot 0 follows this slab's barrier); OLD: slab s - 1 + NSS
         // exists (its later slots go out during this slab's K steps); FINAL: the tile's last slab.
-        auto slab = [&](int s, int buf, auto new_tag, auto old_tag, auto final_tag) __attribute__((always_inline)) {
+        // CHAIN (256-row class followed by another tile of it): the next tile's slab 0 takes the place of "slab NS" --
+        // 1: this is slab NS - 2; after its first K step no copy of this tile is left, the next tile's addresses are
+        //    set up, and slot 0 of that slab 0 follows this slab's barrier;  2: this is slab NS - 1, slot 1 goes out.
+        auto slab = [&](int s, int buf, auto new_tag, auto old_tag, auto final_tag, auto chain_tag) __attribute__((always_inline)) {
             constexpr bool NEW = decltype(new_tag)::value, OLD = decltype(old_tag)::value, FINAL = decltype(final_tag)::value;
+            constexpr int CHAIN = decltype(chain_tag)::value;
+            static_assert(CHAIN == 0 || (C::S2 == 0 && NSS == 2 && !NEW && (CHAIN == 1 ? OLD && !FINAL : !OLD && FINAL)), "chained slabs");
             const int nbuf = buf + 1 == NSS ? 0 : buf + 1;              // buffer of slab s + 1
             const int pbuf = buf == 0 ? NSS - 1 : buf - 1;              // buffer slab s - 1 has left
 #pragma unroll
@@ -697,9 +705,10 @@ void ffn_adaptive_kernel(FfnArgs a) {
                     lds_barrier();
                     rbuf = nbuf; ru = 0;
                 }
-                const int n = last ? (NEW ? C::S0 : 0) : (!OLD ? 0 : (u == 0 ? C::S1 : (u == 1 ? C::S2 : 0)));
+                const int n = last ? (NEW || CHAIN == 1 ? C::S0 : 0)
+                                   : (CHAIN == 2 ? (u == 0 ? C::S1 : 0) : (!OLD ? 0 : (u == 0 ? C::S1 : (u == 1 ? C::S2 : 0))));
                 const int c0 = last ? 0 : (u == 0 ? C::S0 : C::S0 + C::S1);
-                const int cslab = last ? s + NSS : s - 1 + NSS;
+                const int cslab = (CHAIN == 1 && last) || CHAIN == 2 ? 0 : (last ? s + NSS : s - 1 + NSS);
                 const int cbuf = last ? buf : pbuf;
 #pragma unroll
                 for (int i = 0; i < NMF; ++i) {
@@ -721,26 +730,46 @@ void ffn_adaptive_kernel(FfnArgs a) {
                         __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);                              // slab copy
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                if (CHAIN == 1 && u == 0) {                              // this tile's last copies are out
+                    if (chained) setup(tag, nnt);                        // addresses of the next tile
+                }
             }
         };
         {
             const std::true_type T{};
             const std::false_type F{};
-            int buf = 0;
-            auto next = [&]() __attribute__((always_inline)) { buf = buf + 1 == NSS ? 0 : buf + 1; };
-            if (NSS < NS) slab(0, 0, T, F, F); else slab(0, 0, F, F, F);        // (every K here has at least 2 slabs)
-            next();
-            int s = 1;
-            for (; s + NSS < NS; ++s) { slab(s, buf, T, T, F); next(); }
-            if (s + 1 < NS && s - 1 + NSS < NS) { slab(s, buf, F, T, F); next(); ++s; }
-            for (; s + 1 < NS; ++s) { slab(s, buf, F, F, F); next(); }
-            slab(NS - 1, buf, F, F, T);
+            const std::integral_constant<int, 0> C0{};
+            if constexpr (decltype(tag)::value == 0) {
+                // 256-row class: K is a multiple of 128 and at least 256, so NS is even and >= 4; slab s sits in buffer s & 1
+                slab(0, 0, T, F, F, C0);
+                int s = 1;
+                for (; s + 2 < NS; ++s) slab(s, s & 1, T, T, F, C0);
+                // a barrier has passed since the next tile's ticket was written
+                nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]); nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]);
+                ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);
+                chained = nblk >= 0 && ncls == 0 && !(PHASE == 1 && a.row_map);
+                // not chained: the two slots re-fetch this tile's slab 0 into the free buffer 0, which nobody reads
+                slab(NS - 2, 0, F, T, F, std::integral_constant<int, 1>{});
+                slab(NS - 1, 1, F, F, T, std::integral_constant<int, 2>{});
+                if (!chained) wait_vmcnt<0>();                           // ... and is complete before buffer 0 is reused
+            } else {
+                int buf = 0;
+                auto next = [&]() __attribute__((always_inline)) { buf = buf + 1 == NSS ? 0 : buf + 1; };
+                if (NSS < NS) slab(0, 0, T, F, F, C0); else slab(0, 0, F, F, F, C0);        // (every K here has at least 2 slabs)
+                next();
+                int s = 1;
+                for (; s + NSS < NS; ++s) { slab(s, buf, T, T, F, C0); next(); }
+                if (s + 1 < NS && s - 1 + NSS < NS) { slab(s, buf, F, T, F, C0); next(); ++s; }
+                for (; s + 1 < NS; ++s) { slab(s, buf, F, F, F, C0); next(); }
+                slab(NS - 1, buf, F, F, T, C0);
+            }
         }
         lds_barrier();                   // every fragment is in registers: all buffers are free; next ticket visible
-        const int em0 = m0, em_end = m_end, ent = nt;
-        const int nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]), nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]),
-                  ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);    // uniform: keeps the copy descriptors in scalar registers
-        if (nblk >= 0) start_tile(nnt, ncls);                           // the next tile's first slab flies during the epilogue
+        if (!chained) {
+            nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]); nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]);
+            ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);         // uniform: keeps the copy descriptors in scalar registers
+            if (nblk >= 0) start_tile(nnt, ncls);                       // the next tile's first slab flies during the epilogue
+        }
 
         // ---- epilogue.  acc[mb][q][v]: row l31 of row block mb; column 8*(v>>2) + 4*lhi + (v&3) of column block q.
         // A lane holds 4 consecutive columns of one row: stored from there, one instruction would touch 32 rows with
@@ -787,15 +816,20 @@ void ffn_adaptive_kernel(FfnArgs a) {
                             *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) = pack4(hv[0], hv[1], hv[2], hv[3]);
                         }
                 } else {
-                    float gate = 1.0f;
-                    if (scatter && a.row_gate && wrow + mb * 32 + el31 < em_end) gate = a.row_gate[wrow + mb * 32 + el31];
+                    if (scatter && a.row_gate) {                          // router weight of the row
+                        float gate = 1.0f;
+                        if (wrow + mb * 32 + el31 < em_end) gate = a.row_gate[wrow + mb * 32 + el31];
+#pragma unroll
+                        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) acc[mb][q][v] *= gate;
+                    }
 #pragma unroll
                     for (int q = 0; q < NQ; ++q)
 #pragma unroll
                         for (int vg = 0; vg < 4; ++vg)
                             *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) =
-                                pack4(gate * acc[mb][q][vg * 4], gate * acc[mb][q][vg * 4 + 1], gate * acc[mb][q][vg * 4 + 2],
-                                      gate * acc[mb][q][vg * 4 + 3]);
+                                pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
                 }
                 u32x4 v[32 / RPI];
 #pragma unroll
@@ -955,7 +989,8 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     }
     const long long max_blocks = M / bm + G;
     const char* fixed = getenv("MOE_FFN_FIXED_SHAPE");
-    if (bm == 256 && !fp8 && !(fixed && fixed[0] == '1')) return launch_both_adaptive(a, max_blocks, s);
+    // (the adaptive kernel chains tiles over their last two slabs: at least four 64-wide slabs, f >= 256; d always is)
+    if (bm == 256 && !fp8 && f >= 256 && !(fixed && fixed[0] == '1')) return launch_both_adaptive(a, max_blocks, s);
     if (fp8) {
         if (bm == 256) return launch_both<256, true>(a, max_blocks, s);
         if (bm == 128) return launch_both<128, true>(a, max_blocks, s);
