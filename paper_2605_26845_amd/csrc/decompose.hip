@@ -40,6 +40,20 @@ __device__ __forceinline__ int wave_min(int x) {
     return min(min(a, b), min(c, d));
 }
 __device__ __forceinline__ int wave_max(int x) { return -wave_min(-x); }      // callers pass x > INT_MIN
+// Minimum over the first 16 * NW lanes (NW = 1, 2, 4); the reduction inside a 16-lane row folds into the min instruction.
+template <int CTRL>
+__device__ __forceinline__ int min_dpp(int x) { return min(x, __builtin_amdgcn_mov_dpp(x, CTRL, 0xF, 0xF, true)); }
+template <int NW>
+__device__ __forceinline__ int wave_min_rows(int x) {
+    x = min_dpp<0xB1>(x);
+    x = min_dpp<0x4E>(x);
+    x = min_dpp<0x141>(x);
+    x = min_dpp<0x140>(x);
+    int m = __builtin_amdgcn_readlane(x, 0);
+    if (NW > 1) m = min(m, __builtin_amdgcn_readlane(x, 16));
+    if (NW > 2) m = min(min(m, __builtin_amdgcn_readlane(x, 32)), __builtin_amdgcn_readlane(x, 48));
+    return m;
+}
 __device__ __forceinline__ int wave_sum(int x) {
     x += dpp<0xB1>(x);
     x += dpp<0x4E>(x);
@@ -362,7 +376,7 @@ __device__ __forceinline__ void emit_matching(const int (&sigma)[NPL], int durat
 }
 
 // ------------------------------------------------------------------------------ greedy kernel
-template <int NPL, typename T>
+template <int NPL, typename T, int NW>            // NW: 16-lane rows that hold columns (1, 2 or 4)
 __global__ __launch_bounds__(MOE_WAVE)
 void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
                    int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
@@ -424,6 +438,54 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             if (pick >= 0) { set_at<NPL>(p, pick, r, lane); set_at<NPL>(sigma, r, pick, lane); }
         }
         // ---- maximum-weight perfect matching: one shortest augmenting path per row still unmatched
+        if constexpr (NPL == 1) {
+            // One column per lane: Dijkstra form of the search.  dist_j = length of the shortest alternating path found
+            // so far from row r to column j in reduced costs u_i + v_j - R_ij of the duals at the start of the search
+            // (they are updated once, at its end); the set of scanned columns is a scalar bit mask.
+            const bool incol = lane < N;
+            const unsigned long long beyond = N >= 64 ? 0ULL : ~0ULL << N;     // lanes that hold no column count as scanned
+            const T* Rcol = R + (incol ? lane : N - 1);
+            unsigned long long todo = ballot64(incol && sigma[0] < 0);
+            while (todo) {
+                const int r = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                int dist = INT_MAX, way[1] = {-1};
+                unsigned long long used = beyond;
+                int i0 = r, j0 = -1, D = 0;
+                for (int step = 0; step < N; ++step) {
+                    const int base = D + rdlane(u[0], i0);               // row i0 entered the tree at distance D
+                    const bool open = !__builtin_amdgcn_inverse_ballot_w64(used);
+                    const int cand = open ? base + v[0] - (int)Rcol[i0 * N] : INT_MAX;
+                    way[0] = cand < dist ? j0 : way[0];
+                    dist = min(dist, cand);
+                    const int key = open ? dist : INT_MAX;
+                    D = wave_min_rows<NW>(key);                          // (finite: row r is unmatched, so a column is free)
+                    const int j1 = __builtin_ctzll(ballot64(key == D));
+                    used |= 1ULL << j1;
+                    j0 = j1;
+                    i0 = rdlane(p[0], j1);
+                    if (i0 < 0) break;
+                }
+                used &= ~beyond;
+                // duals: a scanned column j rises by D - dist_j, its row falls by the same amount, row r falls by D
+                // (tree edges stay tight, everything stays feasible, the new path is tight)
+                const int sg = sigma[0];
+                const int dcol = __shfl(dist, sg < 0 ? 0 : sg);
+                const bool rin = sg >= 0 && ((used >> sg) & 1ULL);
+                if (__builtin_amdgcn_inverse_ballot_w64(used)) v[0] += D - dist;
+                if (lane == r) u[0] -= D; else if (rin) u[0] -= D - dcol;
+                // flip the path back to row r
+                for (int guard = 0; guard <= N; ++guard) {
+                    int j1 = bcast<NPL>(way, j0);
+                    int i = r;
+                    if (j1 >= 0) i = bcast<NPL>(p, j1);
+                    set_at<NPL>(p, j0, i, lane);
+                    set_at<NPL>(sigma, i, j0, lane);
+                    if (j1 < 0) break;
+                    j0 = j1;
+                }
+            }
+        } else
         for (int r = 0; r < N; ++r) {
             if (bcast<NPL>(sigma, r) >= 0) continue;
             int minv[NPL], way[NPL];
@@ -902,8 +964,10 @@ extern "C" moe_status moe_decompose_greedy(const int32_t* mats, int B, int N, in
     const bool narrow = (flags & MOE_DECOMP_ENTRIES_U16) != 0;
     const size_t lds = (size_t)N * N * (narrow ? sizeof(uint16_t) : sizeof(int32_t));
     moe::LaunchScope k("greedy_kernel", s);
-    auto kern = N <= 64 ? (narrow ? greedy_kernel<1, uint16_t> : greedy_kernel<1, int32_t>)
-                        : (narrow ? greedy_kernel<2, uint16_t> : greedy_kernel<2, int32_t>);
+    auto kern = N <= 16   ? (narrow ? greedy_kernel<1, uint16_t, 1> : greedy_kernel<1, int32_t, 1>)
+                : N <= 32 ? (narrow ? greedy_kernel<1, uint16_t, 2> : greedy_kernel<1, int32_t, 2>)
+                : N <= 64 ? (narrow ? greedy_kernel<1, uint16_t, 4> : greedy_kernel<1, int32_t, 4>)
+                          : (narrow ? greedy_kernel<2, uint16_t, 4> : greedy_kernel<2, int32_t, 4>);
     hipLaunchKernelGGL(kern, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts, residual,
                        (unsigned long long*)hashes);
     return k.done();
