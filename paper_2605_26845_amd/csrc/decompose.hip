@@ -43,6 +43,19 @@ __device__ __forceinline__ int wave_max(int x) { return -wave_min(-x); }      //
 // Minimum over the first 16 * NW lanes (NW = 1, 2, 4); the reduction inside a 16-lane row folds into the min instruction.
 template <int CTRL>
 __device__ __forceinline__ int min_dpp(int x) { return min(x, __builtin_amdgcn_mov_dpp(x, CTRL, 0xF, 0xF, true)); }
+template <int CTRL>
+__device__ __forceinline__ int max_dpp(int x) { return max(x, __builtin_amdgcn_mov_dpp(x, CTRL, 0xF, 0xF, true)); }
+template <int NW>
+__device__ __forceinline__ int wave_max_rows(int x) {
+    x = max_dpp<0xB1>(x);
+    x = max_dpp<0x4E>(x);
+    x = max_dpp<0x141>(x);
+    x = max_dpp<0x140>(x);
+    int m = __builtin_amdgcn_readlane(x, 0);
+    if (NW > 1) m = max(m, __builtin_amdgcn_readlane(x, 16));
+    if (NW > 2) m = max(max(m, __builtin_amdgcn_readlane(x, 32)), __builtin_amdgcn_readlane(x, 48));
+    return m;
+}
 template <int NW>
 __device__ __forceinline__ int wave_min_rows(int x) {
     x = min_dpp<0xB1>(x);
@@ -418,6 +431,26 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
         for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
         // ---- row reduction: lower u_r until row r has a tight edge, and take that edge if its column is free.
         //      (Duals stay feasible, matched edges are tight; most rows are settled here and skip the search.)
+        if constexpr (NPL == 1) {
+            // u_r <- max_j (R_rj - v_j) does not depend on the other rows: only the set of taken columns (a scalar
+            // mask) links the iterations, so their LDS reads and reductions overlap
+            const bool incol = lane < N;
+            const T* Rcol = R + (incol ? lane : N - 1);
+            unsigned long long taken = 0;
+#pragma unroll 4
+            for (int r = 0; r < N; ++r) {
+                const int x = incol ? (int)Rcol[r * N] - v[0] : INT_MIN;  // lanes without a column never win or tie
+                const int m = wave_max_rows<NW>(x);
+                const unsigned long long avail = ballot64(x == m) & ~taken;
+                if (lane == r) u[0] = m;
+                if (avail) {
+                    const int pick = __builtin_ctzll(avail);
+                    taken |= 1ULL << pick;
+                    if (lane == pick) p[0] = r;
+                    if (lane == r) sigma[0] = pick;
+                }
+            }
+        } else
         for (int r = 0; r < N; ++r) {
             const int ur = bcast<NPL>(u, r);
             int slack[NPL], local = INT_MAX;
