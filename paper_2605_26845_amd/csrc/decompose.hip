@@ -207,6 +207,7 @@ template <int NPL, typename T, typename Pred>
 __device__ __forceinline__ void build_masks(const T* R, int N, int lane, Mask<NPL> (&tm)[NPL], Pred pred) {
 #pragma unroll
     for (int s = 0; s < NPL; ++s) tm[s].clear();
+#pragma unroll 4
     for (int i = 0; i < N; ++i) {
         Mask<NPL> row;
 #pragma unroll
@@ -429,6 +430,14 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
     while (t < kmax && nnz > 0) {
 #pragma unroll
         for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
+        // N <= 16: this lane's column of the residual sits in registers for the whole matching (a row picked at run time
+        // is then a register selected by a scalar index, not an LDS round trip)
+        int Rc[NW == 1 ? 16 : 1];
+        if constexpr (NW == 1) {
+            const T* col = R + (lane < N ? lane : N - 1);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Rc[i] = i < N ? (int)col[i * N] : 0;
+        }
         // ---- row reduction: lower u_r until row r has a tight edge, and take that edge if its column is free.
         //      (Duals stay feasible, matched edges are tight; most rows are settled here and skip the search.)
         if constexpr (NPL == 1) {
@@ -437,9 +446,8 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             const bool incol = lane < N;
             const T* Rcol = R + (incol ? lane : N - 1);
             unsigned long long taken = 0;
-#pragma unroll 4
-            for (int r = 0; r < N; ++r) {
-                const int x = incol ? (int)Rcol[r * N] - v[0] : INT_MIN;  // lanes without a column never win or tie
+            auto reduce_row = [&](int r, int entry) __attribute__((always_inline)) {
+                const int x = incol ? entry - v[0] : INT_MIN;             // lanes without a column never win or tie
                 const int m = wave_max_rows<NW>(x);
                 const unsigned long long avail = ballot64(x == m) & ~taken;
                 if (lane == r) u[0] = m;
@@ -449,6 +457,14 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                     if (lane == pick) p[0] = r;
                     if (lane == r) sigma[0] = pick;
                 }
+            };
+            if constexpr (NW == 1) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (r < N) reduce_row(r, Rc[r]);
+            } else {
+#pragma unroll 4
+                for (int r = 0; r < N; ++r) reduce_row(r, (int)Rcol[r * N]);
             }
         } else
         for (int r = 0; r < N; ++r) {
@@ -488,7 +504,9 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                 for (int step = 0; step < N; ++step) {
                     const int base = D + rdlane(u[0], i0);               // row i0 entered the tree at distance D
                     const bool open = !__builtin_amdgcn_inverse_ballot_w64(used);
-                    const int cand = open ? base + v[0] - (int)Rcol[i0 * N] : INT_MAX;
+                    int entry;
+                    if constexpr (NW == 1) entry = Rc[i0 & 15]; else entry = (int)Rcol[i0 * N];
+                    const int cand = open ? base + v[0] - entry : INT_MAX;
                     way[0] = cand < dist ? j0 : way[0];
                     dist = min(dist, cand);
                     const int key = open ? dist : INT_MAX;
@@ -580,7 +598,17 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             int vv[NPL];
 #pragma unroll
             for (int s = 0; s < NPL; ++s) vv[s] = v[s];
-            build_masks<NPL, T>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
+            if constexpr (NW == 1) {
+                tm[0].clear();
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (i < N) {
+                        const unsigned long long row = ballot64(lane < N && __builtin_amdgcn_readlane(u[0], i) + vv[0] == Rc[i]);
+                        if (lane == i) tm[0].w[0] = row;
+                    }
+            } else {
+                build_masks<NPL, T>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
+            }
         }
         lex_smallest<NPL>(tm, N, lane, sigma, p, 0);
         // ---- ship whole entries; the matching lasts as long as its heaviest pair
