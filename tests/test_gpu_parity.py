@@ -378,6 +378,36 @@ def test_ffn_small(lib, dtype, tile_rows, E_loc, d, f, M, S):
         os.environ.pop("MOE_FFN_ROWS", None)
 
 
+def test_ffn_buffers_at_addresses_with_bit_31_set(lib):
+    """Output and workspace whose 64-bit addresses have bit 31 of the low word set (the kernels build buffer
+    descriptors from the two halves of such addresses)."""
+    say("ffn buffers above a 2 GiB boundary of the low address word")
+    E_loc, d, f, M, S = 1, 256, 512, 700, 3
+    W = workloads.ffn_weights(E_loc, d, f, seed=d + f)
+    x = workloads.activations(M, d, seed=M)
+    offsets = workloads.random_offsets(S * E_loc, M, seed=M + S)
+    ws_bytes = lib.moe_ffn_workspace_bytes(M, d, f)
+    y_bytes = M * d * 2
+    pool = torch.empty(((1 << 32) + (64 << 20),), dtype=torch.uint8, device=DEV)
+    low = pool.data_ptr() & 0xFFFFFFFF
+    o = ((0x80000000 - low) % (1 << 32) + 255) // 256 * 256 + 4096
+    o2 = (o + y_bytes + 255) // 256 * 256
+    assert ((pool.data_ptr() + o) >> 31) & 1 and ((pool.data_ptr() + o2) >> 31) & 1 and o2 + ws_bytes <= pool.numel()
+    y0 = pool[o:o + y_bytes].view(torch.bfloat16).view(M, d)
+    ws = pool[o2:o2 + ws_bytes]
+    for rows in ("256", "128"):
+        os.environ["MOE_FFN_ROWS"] = rows
+        try:
+            y = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(offsets), S, E_loc, y=y0, workspace=ws, **upload_weights(W))
+            torch.cuda.synchronize()
+        finally:
+            os.environ.pop("MOE_FFN_ROWS", None)
+        err = ffn_error(host_bf16_bits(y), oracle.expert_ffn_sliced(x, offsets, E_loc, W), offsets)
+        say("   rows", rows, "max relative error", err)
+        assert err <= FFN_TOL["bf16"]
+    del pool, y0, ws, y
+
+
 def test_ffn_edge_cases(lib):
     say("ffn edge cases")
     E_loc, d, f = 2, 256, 128
