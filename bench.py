@@ -69,7 +69,7 @@ def summarize_counters(workload, fetch_csv, write_csv):
                "traffic_bytes_per_launch": detail["ffn_gemm1_kernel"]["total_bytes"], "detail": detail,
                "see": "profiles/ffn_%s_hbm_traffic.md" % workload}, open(base + ".json", "w"), indent=1)
     lines = ["# HBM-side byte counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels (gemm1 = phase 1: gate/up + SwiGLU)" % workload,
-             "", "Commands (run from /tmp with TMPDIR=/tmp on the MI355X box, one counter per run; then the summary, no GPU needed):", ""]
+             "", "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box, one counter per run; then the summary, no GPU needed):", ""]
     for c in ("FETCH_SIZE", "WRITE_SIZE"):
         lines.append("    rocprofv3 --pmc %s --output-format csv -d gpurun_out/pmc_%s -o p -- python3 bench.py --workload %s --steps 10 "
                      "--warmup 2 --no-extras --no-cpu-baseline --calibration-copy" % (c, c, workload))
