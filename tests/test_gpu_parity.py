@@ -100,7 +100,9 @@ def check_decomposition(lib, which, mats, kmax, zero_diag):
     assert np.array_equal(lean["counts"].cpu().numpy(), ref["counts"])
 
 
-SHAPES = [(1, 1.0, 10), (2, 1.0, 3), (3, 0.7, 4), (5, 0.6, 2), (8, 1.0, 1000), (16, 0.5, 30), (33, 0.3, 5),
+# (N <= 16, <= 32, <= 64 and > 64 take different code paths in the greedy kernel)
+SHAPES = [(1, 1.0, 10), (2, 1.0, 3), (3, 0.7, 4), (5, 0.6, 2), (8, 1.0, 1000), (15, 0.9, 77), (16, 0.5, 30),
+          (16, 1.0, 100000000), (17, 0.6, 50), (24, 0.4, 7), (32, 0.9, 3000), (33, 0.3, 5),
           (64, 1.0, 100000), (65, 0.4, 9), (100, 0.8, 3), (128, 0.6, 40000)]
 
 
