@@ -38,6 +38,18 @@ def parse():
     return ap.parse_args()
 
 
+def code_digest(path):
+    """SHA-256 of a source file without its // comments and blank space: a stored counter figure stays valid across
+    edits that cannot change the kernel."""
+    import hashlib, re
+    lines = []
+    for line in open(path, encoding="utf-8"):
+        line = re.sub(r"//.*$", "", line).strip()
+        if line:
+            lines.append(re.sub(r"\s+", " ", line))
+    return hashlib.sha256("\n".join(lines).encode()).hexdigest()
+
+
 def summarize_counters(workload, fetch_csv, write_csv):
     """FETCH_SIZE / WRITE_SIZE (KiB per dispatch) of the two FFN kernels, scaled by what the same counter reads for the
     256 MiB calibration copy; stored with the SHA-256 of the kernel source it was measured on."""
@@ -63,7 +75,7 @@ def summarize_counters(workload, fetch_csv, write_csv):
         rb, wb = f[k] * cal_f * 1024, w[k] * cal_w * 1024
         detail[k] = {"read_bytes": rb, "write_bytes": wb, "total_bytes": rb + wb}
     rel = "paper_2605_26845_amd/csrc/ffn.hip"
-    sha = hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest()
+    sha = code_digest(os.path.join(ROOT, rel))
     base = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic" % workload)
     json.dump({"kernel": "ffn_gemm1_kernel", "workload": workload, "source_sha256": {rel: sha},
                "traffic_bytes_per_launch": detail["ffn_gemm1_kernel"]["total_bytes"], "detail": detail,
@@ -92,7 +104,7 @@ def summarize_counters(workload, fetch_csv, write_csv):
               % (M, cfg.d, cfg.f, cfg.E_loc, xb / 1e6, wb_ / 1e6),
               "h %.1f MB written = %.1f MB." % (hb / 1e6, (xb + wb_ + hb) / 1e6)]
     lines += ["The fetch counter sits between the L2 and the fabric: it also counts reads served by the 256 MB memory-side cache.",
-              "The stored figure (`.json`) carries the SHA-256 of ffn.hip it was measured on; bench.py reports it as `roofline.traffic` only while that matches.", ""]
+              "The stored figure (`.json`) carries the SHA-256 of ffn.hip (comments and blank space removed) it was measured on; bench.py reports it as `roofline.traffic` only while that matches.", ""]
     open(base + ".md", "w").write("\n".join(lines))
     print(base + ".md")
 
@@ -253,7 +265,7 @@ def stored_traffic(workload):
     try:
         rec = json.load(open(path))
         for rel, digest in rec["source_sha256"].items():
-            if hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest() != digest:
+            if code_digest(os.path.join(ROOT, rel)) != digest:
                 return None
         return rec["traffic_bytes_per_launch"]
     except (OSError, KeyError, ValueError):

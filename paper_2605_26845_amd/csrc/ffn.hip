@@ -635,8 +635,9 @@ void ffn_adaptive_kernel(FfnArgs a) {
         else               { setup(std::integral_constant<int, 2>{}, nt_); prologue(std::integral_constant<int, 2>{}, 0, 1); }
     };
 
-    // One tile of the class given by `tag`; its first NSS slabs are in flight.  Returns the class of the next tile
-    // (whose first slabs it has issued before its own epilogue) or -1.
+    // One tile of the class given by `tag`; its slab 0 is in flight (the other buffers may hold the previous tile's
+    // output staging and are filled after the opening barrier).  Returns the class of the next tile (whose slab 0 it
+    // has issued in its last slabs or before its own read-out) or -1.
     auto run_tile = [&](auto tag) __attribute__((always_inline)) -> int {
         typedef Cls<decltype(tag)::value> C;
         constexpr int MB = C::MB, NQ = C::NQ, NSS = C::NSS, SUB = C::SUB;
