@@ -177,7 +177,9 @@ moe_status moe_slice_table_rows(const int32_t* ids, int N, int T, int topk, int 
  *                   (MOE_W_FP8_E4M3_B128 only, else NULL): weight = decode(code) * scale
  *   y          out  bf16 [M][d]; rows >= offsets[last] are left untouched
  *   workspace       moe_ffn_workspace_bytes(M, d, f) bytes (holds the hidden activations)
- * Limits: d % 256 == 0, f % 128 == 0, S*E_loc <= 65536, M*max(d,f) < 2^31.
+ * Limits: d % 256 == 0, f % 128 == 0, S*E_loc <= 65536, M*max(d,f) < 2^31; x, y, the weights and
+ * the workspace 16-byte aligned (MOE_ERR_INVALID_ARG otherwise).  The sigmoid inside silu uses the
+ * hardware reciprocal (within 1 ulp of the quotient, before the rounding to bf16).
  * ------------------------------------------------------------------------------------------- */
 size_t     moe_ffn_workspace_bytes(int M, int d, int f);
 moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, int S, int E_loc,

@@ -960,6 +960,9 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     if ((long long)M * (d > f ? d : f) >= (1LL << 31)) return MOE_ERR_UNSUPPORTED_SHAPE;
     if (M == 0 || G == 0) return MOE_OK;
     if (!x || !y) return MOE_ERR_INVALID_ARG;
+    // every operand is moved in 16-byte pieces
+    if ((((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_gate | (uintptr_t)w_up | (uintptr_t)w_down | (uintptr_t)workspace) & 15) != 0)
+        return MOE_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < moe_ffn_workspace_bytes(M, d, f)) return MOE_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
 

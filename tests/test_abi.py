@@ -40,6 +40,14 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.moe_expert_ffn_sliced(ctypes.c_void_p(8), ctypes.c_void_p(8), 4, 1, 1, 100, 128, 0, ctypes.c_void_p(8),
                                    ctypes.c_void_p(8), ctypes.c_void_p(8), None, None, None, ctypes.c_void_p(8),
                                    None, 0, None) == -2                                  # d % 256 != 0
+    # operands are moved in 16-byte pieces: a pointer that is only 8-byte aligned is refused, before the workspace check
+    ok, odd = ctypes.c_void_p(4096), ctypes.c_void_p(4104)
+    for bad in range(5):
+        ptrs = [odd if k == bad else ok for k in range(5)]                                # x, w_gate, w_up, w_down, y
+        assert L.moe_expert_ffn_sliced(ptrs[0], ctypes.c_void_p(8), 4, 1, 1, 256, 128, 0, ptrs[1], ptrs[2], ptrs[3],
+                                       None, None, None, ptrs[4], ok, 1 << 30, None) == -1
+    assert L.moe_expert_ffn_sliced(ok, ctypes.c_void_p(8), 4, 1, 1, 256, 128, 0, ok, ok, ok, None, None, None, ok,
+                                   None, 0, None) == -3                                  # aligned, workspace missing
     assert L.moe_kernel_timing_read(None, None, None, 0) == 0
 
 
