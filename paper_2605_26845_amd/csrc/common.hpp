@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include "../../include/moe_circuit.h"
 
+#include <atomic>
+
 namespace moe {
 
 void        note_hip_error(hipError_t e, const char* what);
@@ -26,6 +28,16 @@ struct LaunchScope {
         if (e != hipSuccess) { note_hip_error(e, "kernel launch"); return MOE_ERR_HIP; }
         return MOE_OK;
     }
+};
+
+// "Done once per device" for set-up that HIP keeps per device (function attributes): bit d = done on device d.
+struct DeviceOnce {
+    std::atomic<unsigned long long> done{0};
+    bool needed(int& dev) {
+        if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+        return dev < 0 || dev >= 64 || !((done.load(std::memory_order_acquire) >> dev) & 1ULL);
+    }
+    void mark(int dev) { if (dev >= 0 && dev < 64) done.fetch_or(1ULL << dev, std::memory_order_release); }
 };
 
 }  // namespace moe

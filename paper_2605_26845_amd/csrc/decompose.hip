@@ -1061,12 +1061,13 @@ extern "C" moe_status moe_decompose_sinkhorn_bvn(const int32_t* mats, int B, int
     if (B == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)hip_stream;
     const size_t lds = (size_t)N * N * sizeof(double);
-    static bool attr_done = false;
-    if (!attr_done) {
+    static moe::DeviceOnce attr;
+    int dev;
+    if (attr.needed(dev)) {
         hipError_t e = hipFuncSetAttribute((const void*)sinkhorn_bvn_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            MOE_MAX_RANKS * MOE_MAX_RANKS * (int)sizeof(double));
         if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
-        attr_done = true;
+        attr.mark(dev);
     }
     moe::LaunchScope k("sinkhorn_bvn_kernel", s);
     if (N <= 64)

@@ -868,17 +868,16 @@ void ffn_adaptive_kernel(FfnArgs a) {
 int plan_capacity(int M) { return M / 64 + MAX_GROUPS + 1; }
 size_t h_bytes(int M, int f) { return (((size_t)M * f * 2) + 255) & ~(size_t)255; }
 
-int g_num_cus = 0;
+std::atomic<int> g_num_cus[64];            // compute units of device d (0 = not asked yet)
 int num_cus() {
-    if (g_num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            g_num_cus = n;
-        else
-            g_num_cus = 256;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    n = g_num_cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        g_num_cus[dev].store(n, std::memory_order_relaxed);
     }
-    return g_num_cus;
+    return n;
 }
 
 // Tile shapes.  ROWS = rows per tile:
@@ -894,12 +893,13 @@ template <int PHASE, int ROWS, bool FP8>
 moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     typedef Shape<ROWS> S;
     constexpr size_t lds = (size_t)S::NST * (ROWS + BN) * S::BK * 2;
-    static bool attr_done = false;
+    static moe::DeviceOnce attr;
     auto kern = ffn_gemm_kernel<PHASE, S::WMW, S::MB, FP8, S::BK, S::NST, S::PER_CU>;
-    if (!attr_done) {
+    int dev;
+    if (attr.needed(dev)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
-        attr_done = true;
+        attr.mark(dev);
     }
     const long long slots = (long long)num_cus() * S::PER_CU;
     const int grid = (int)(max_tiles < slots ? max_tiles : slots);
@@ -910,12 +910,13 @@ moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
 
 template <int PHASE>
 moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s) {
-    static bool attr_done = false;
+    static moe::DeviceOnce attr;
     auto kern = ffn_adaptive_kernel<PHASE>;
-    if (!attr_done) {
+    int dev;
+    if (attr.needed(dev)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ADAPTIVE_LDS);
         if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
-        attr_done = true;
+        attr.mark(dev);
     }
     const long long slots = num_cus();
     const int grid = (int)(max_tiles < slots ? max_tiles : slots);
