@@ -44,7 +44,8 @@ typedef int moe_status;
 
 /* weight formats of moe_expert_ffn_sliced */
 #define MOE_W_BF16            0   /* bfloat16                                                     */
-#define MOE_W_FP8_E4M3_B128   1   /* OCP FP8 E4M3 codes + one float scale per 128 x 128 block      */
+#define MOE_W_FP8_E4M3_B128   1   /* OCP FP8 E4M3 codes (S.1111.111 = NaN, no infinities) + one float
+                                     scale per 128 x 128 block                                   */
 
 /* ---------------------------------------------------------------------------------------------
  * moe_route_histogram -- Section 2.1 (dispatch) / Section 3 (the all-to-all communication

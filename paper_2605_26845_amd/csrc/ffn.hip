@@ -97,23 +97,14 @@ __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
     return __builtin_bit_cast(u32x2, v);
 }
 
-// OCP FP8 E4M3 code -> float (bias 7, subnormals at exponent field 0, no infinities).
-__device__ __forceinline__ float e4m3_to_float(unsigned int c) {
-    unsigned int sign = (c & 0x80u) << 24, e = (c >> 3) & 0xFu, m = c & 0x7u;
-    float sub = (float)m * 0.001953125f;                                  // m * 2^-9
-    float nor = __uint_as_float(((e + 120u) << 23) | (m << 20));
-    float mag = e == 0 ? sub : nor;
-    return __uint_as_float(__float_as_uint(mag) | sign);
-}
-// 8 consecutive fp8 codes (8 bytes) times one scale -> 8 bf16
+// 8 consecutive OCP FP8 E4M3 codes (8 bytes; bias 7, subnormals at exponent field 0, no infinities, S.1111.111 = NaN)
+// times one scale -> 8 bf16.  gfx950 decodes two codes per v_cvt_pk_f32_fp8.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ u32x4 dequant8(u32x2 codes, float scale) {
-    float v[8];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        v[k] = e4m3_to_float((codes.x >> (8 * k)) & 0xFFu) * scale;
-        v[4 + k] = e4m3_to_float((codes.y >> (8 * k)) & 0xFFu) * scale;
-    }
-    bf16x8 o = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3], (__bf16)v[4], (__bf16)v[5], (__bf16)v[6], (__bf16)v[7]};
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.x, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.y, true);
+    bf16x8 o = {(__bf16)(a.x * scale), (__bf16)(a.y * scale), (__bf16)(b.x * scale), (__bf16)(b.y * scale),
+                (__bf16)(c.x * scale), (__bf16)(c.y * scale), (__bf16)(d.x * scale), (__bf16)(d.y * scale)};
     return __builtin_bit_cast(u32x4, o);
 }
 
