@@ -177,12 +177,17 @@ moe_status moe_slice_table_rows(const int32_t* ids, int N, int T, int topk, int 
  *   s_gate,s_up in  float [E_loc][f/128][d/128], s_down float [E_loc][d/128][f/128]
  *                   (MOE_W_FP8_E4M3_B128 only, else NULL): weight = decode(code) * scale
  *   y          out  bf16 [M][d]; rows >= offsets[last] are left untouched
- *   workspace       moe_ffn_workspace_bytes(M, d, f) bytes (holds the hidden activations)
+ *   workspace       moe_ffn_workspace_bytes(M, d, f) bytes (holds the hidden activations).  With
+ *                   MOE_W_FP8_E4M3_B128 the caller may add moe_ffn_expanded_weights_bytes(E_loc, d, f)
+ *                   bytes: when there are at least 2048 rows per local expert on average the weights
+ *                   are then expanded to bf16 once per call (the same values the kernels would form
+ *                   tile by tile) and the faster bf16 kernels run
  * Limits: d % 256 == 0, f % 128 == 0, S*E_loc <= 65536, M*max(d,f) < 2^31; x, y, the weights and
  * the workspace 16-byte aligned (MOE_ERR_INVALID_ARG otherwise).  The sigmoid inside silu uses the
  * hardware reciprocal (within 1 ulp of the quotient, before the rounding to bf16).
  * ------------------------------------------------------------------------------------------- */
 size_t     moe_ffn_workspace_bytes(int M, int d, int f);
+size_t     moe_ffn_expanded_weights_bytes(int E_loc, int d, int f);
 moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offsets, int M, int S, int E_loc,
                                  int d, int f, int weight_format,
                                  const void* w_gate, const void* w_up, const void* w_down,

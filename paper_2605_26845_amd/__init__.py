@@ -27,7 +27,7 @@ _STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED_SHAP
 
 EXPORTS = [
     "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
-    "moe_slice_table", "moe_ffn_workspace_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
+    "moe_slice_table", "moe_ffn_workspace_bytes", "moe_ffn_expanded_weights_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped",
 ]
@@ -97,6 +97,8 @@ def load():
     L.moe_expert_ffn_sliced_mapped.restype = ci
     L.moe_ffn_workspace_bytes.argtypes = [ci, ci, ci]
     L.moe_ffn_workspace_bytes.restype = sz
+    L.moe_ffn_expanded_weights_bytes.argtypes = [ci, ci, ci]
+    L.moe_ffn_expanded_weights_bytes.restype = sz
     L.moe_expert_ffn_sliced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moe_expert_ffn_sliced.restype = ci
     L.moe_kernel_timing_enable.argtypes = [ci]
@@ -278,6 +280,11 @@ def moe_ffn_workspace_bytes(M: int, d: int, f: int) -> int:
     return int(load().moe_ffn_workspace_bytes(M, d, f))
 
 
+def moe_ffn_expanded_weights_bytes(E_loc: int, d: int, f: int) -> int:
+    """Extra workspace that lets a call with fp8 weights and many rows expand them to bf16 once."""
+    return int(load().moe_ffn_expanded_weights_bytes(E_loc, d, f))
+
+
 def moe_expert_ffn_sliced_mapped(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, row_map, row_gate=None,
                                  s_gate=None, s_up=None, s_down=None, y=None, workspace=None):
     """As moe_expert_ffn_sliced with x and y in arrival order: schedule row m is row row_map[m] of both, and its
@@ -313,6 +320,8 @@ def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, 
     _dev_check(y, torch.bfloat16, "y")
     need = moe_ffn_workspace_bytes(M, d, f)
     if workspace is None:
+        if fp8 and M >= 2048 * E_loc:
+            need += moe_ffn_expanded_weights_bytes(E_loc, d, f)
         workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=x.device)
     if _row_map is not None or _row_gate is not None:
         _check(load().moe_expert_ffn_sliced_mapped(_ptr(x), _ptr(offsets), M, S, E_loc, d, f,

@@ -410,6 +410,33 @@ def test_ffn_buffers_at_addresses_with_bit_31_set(lib):
     del pool, y0, ws, y
 
 
+def test_ffn_fp8_weights_expanded_once(lib):
+    """With room in the workspace and >= 2048 rows per expert the fp8 weights are expanded to bf16 before the GEMMs:
+    same values, so the same result up to the order of the fp32 sums."""
+    say("ffn fp8: weights expanded to bf16 once per call")
+    E_loc, d, f, M, S = 2, 256, 384, 4500, 3
+    W = workloads.ffn_weights(E_loc, d, f, seed=77, dtype="fp8")
+    x = workloads.activations(M, d, seed=78)
+    offsets = workloads.random_offsets(S * E_loc, M, seed=79)
+    up = upload_weights(W)
+    base = lib.moe_ffn_workspace_bytes(M, d, f)
+    extra = lib.moe_ffn_expanded_weights_bytes(E_loc, d, f)
+    assert extra >= 3 * E_loc * d * f * 2
+    ref = oracle.expert_ffn_sliced(x, offsets, E_loc, W)
+    outs = []
+    for nbytes in (base, base + extra):
+        ws = torch.empty((nbytes,), dtype=torch.uint8, device=DEV)
+        y = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(offsets), S, E_loc, workspace=ws, **up)
+        torch.cuda.synchronize()
+        yb = host_bf16_bits(y)
+        err = ffn_error(yb, ref, offsets)
+        say("   workspace", nbytes, "max relative error", err)
+        assert err <= FFN_TOL["fp8"]
+        outs.append(oracle.decode_bf16(yb))
+    scale = np.abs(outs[0]).max()
+    assert np.abs(outs[0] - outs[1]).max() <= 0.02 * scale
+
+
 def test_ffn_edge_cases(lib):
     say("ffn edge cases")
     E_loc, d, f = 2, 256, 128
