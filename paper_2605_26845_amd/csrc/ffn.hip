@@ -48,43 +48,72 @@ __device__ __forceinline__ int mapped_row(const FfnArgs& a, int m) { return a.ro
 // Splits every group into row blocks of BM rows.  One workgroup.  Malformed offsets cannot make
 // it write outside the table: boundaries are clamped to [0, M] and to non-decreasing order, and
 // entries beyond `cap` are dropped.
+// Plan entry = (first row, end of the group, local expert, shape class of the block: 0 for more than 128 rows, else 1).
+// The partial last blocks of the groups come first in the table and the full blocks after them: a partial block's
+// tiles take longer than a full block's (they read twice the weights per MFMA), and a long tile handed out late is
+// what the whole launch then waits for.  (A third class of 64 rows x 1024 columns for blocks of <= 64 rows was
+// measured: its tiles take twice as long as any other and made phase 1 of the bench schedule 7 % slower by finishing
+// last; it is not in the kernel.)
+__device__ __forceinline__ int plan_scan(int v, int tid, int* wave_tot, int& total) {       // exclusive prefix over the workgroup
+    const int lane = tid & 63, wave = tid >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int base = 0;
+    total = 0;
+    for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+        if (w < wave) base += wave_tot[w];
+        total += wave_tot[w];
+    }
+    return base + incl - v;
+}
+
 __global__ __launch_bounds__(PLAN_THREADS)
 void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int M, int bm, int cap, int4* __restrict__ plan) {
-    // plan entry = (first row, end of the group, local expert, shape class of the block: 0 for > 128 rows, 1 for > 64, else 2)
     __shared__ int wave_tot[PLAN_THREADS / 64];
-    __shared__ int running;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) running = 0;
-    __syncthreads();
-    for (int g0 = 0; g0 < G; g0 += PLAN_THREADS) {
-        const int g = g0 + tid;
-        int lo = 0, hi = 0;
+    const int tid = threadIdx.x;
+    auto bounds = [&](int g, int& lo, int& hi) {
+        lo = hi = 0;
         if (g < G) {
             lo = min(max(offsets[g], 0), M);
             hi = min(max(offsets[g + 1], lo), M);
         }
-        const int nblk = (hi - lo + bm - 1) / bm;
-        int incl = nblk;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int o = __shfl_up(incl, off);
-            if (lane >= off) incl += o;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        int base = running;
-        for (int w = 0; w < wave; ++w) base += wave_tot[w];
-        int start = base + incl - nblk;
-        for (int k = 0; k < nblk; ++k)
-            if (start + k < cap) {
-                const int left = hi - (lo + k * bm);
-                plan[PLAN_HDR + start + k] = make_int4(lo + k * bm, hi, g % e_loc, left > 128 ? 0 : (left > 64 ? 1 : 2));
-            }
-        __syncthreads();
-        if (tid == PLAN_THREADS - 1) running = base + incl;
-        __syncthreads();
+    };
+    // ---- number of partial blocks (groups whose size is not a multiple of bm)
+    int partial = 0;
+    for (int g = tid; g < G; g += PLAN_THREADS) {
+        int lo, hi;
+        bounds(g, lo, hi);
+        partial += (hi - lo) % bm != 0;
     }
-    if (tid == 0) plan[0] = make_int4(min(running, cap), 0, 0, 0);
+    int n_partial;
+    plan_scan(partial, tid, wave_tot, n_partial);
+    // ---- table: partial blocks in group order, then the full blocks in group order
+    int run_partial = 0, run_full = n_partial;                        // (uniform: every thread adds the same totals)
+    for (int g0 = 0; g0 < G; g0 += PLAN_THREADS) {
+        const int g = g0 + tid;
+        int lo, hi;
+        bounds(g, lo, hi);
+        const int rows = hi - lo, nfull = rows / bm, has_partial = rows % bm != 0;
+        int tot;
+        const int at_partial = run_partial + plan_scan(has_partial, tid, wave_tot, tot);
+        run_partial += tot;
+        int at_full = run_full + plan_scan(nfull, tid, wave_tot, tot);
+        run_full += tot;
+        for (int k = 0; k < nfull; ++k, ++at_full)
+            if (at_full < cap) plan[PLAN_HDR + at_full] = make_int4(lo + k * bm, hi, g % e_loc, bm > 128 ? 0 : 1);
+        if (has_partial && at_partial < cap) {
+            const int row = lo + nfull * bm;
+            plan[PLAN_HDR + at_partial] = make_int4(row, hi, g % e_loc, hi - row > 128 ? 0 : 1);
+        }
+    }
+    if (tid == 0) plan[0] = make_int4(min(run_full, cap), 0, 0, 0);
     if (tid >= 1 && tid < PLAN_HDR) plan[tid] = make_int4(0, 0, 0, 0);      // tile queue counters
 }
 
@@ -464,10 +493,10 @@ void ffn_gemm_kernel(FfnArgs a) {
 // per row block so that ragged slices do not pay for 256 rows they do not have:
 //   class 0: 4 x 2 wavefronts = 256 rows x 256 columns;  64-wide K slabs (128-byte rows) of 64 KiB, two in LDS
 //   class 1: 2 x 4            = 128 rows x 512 columns;  32-wide K slabs (64-byte rows) of 40 KiB, three in LDS
-//   class 2: 1 x 8            =  64 rows x 1024 columns; 32-wide K slabs of 68 KiB, two in LDS
-// Every class runs the same number of MFMAs per tile; a block of <= 64 rows needs a quarter of the tiles of class 0.
+// Both classes run the same number of MFMAs per tile.  (A 1 x 8 arrangement of 64 rows x 1024 columns was measured
+// too: its tiles read four times the weights per row and take twice as long as the others -- see the plan kernel.)
 // Columns come in units (phase 1: 128 hidden units = 128 gate + 128 up rows; phase 2: 256 rows of w_down); a tile of
-// class c covers 1 / 2 / 4 consecutive units.  A unit past the end is fetched as the last valid one and not stored.
+// class c covers 1 / 2 consecutive units.  A unit past the end is fetched as the last valid one and not stored.
 // The 256-row class, which does most of the work, has 128-byte slab rows so that every copy fetches whole cache
 // lines: a 64-byte row is half a line whose other half is requested again by the next slab, which doubles the
 // requests to the L2 and the fill traffic into the L1 and keeps the address FIFO of the memory pipeline full (and
@@ -475,7 +504,8 @@ void ffn_gemm_kernel(FfnArgs a) {
 // The barrier at the end of slab s publishes slab s + 1 and frees the buffer of slab s; the copies of slab s + NSS
 // go out from there on, spaced between the MFMAs (slot 0 = rest of slab s, slot i = K step i - 1 of slab s + 1).
 template <int CLS> struct Cls {
-    static constexpr int WMW = CLS == 0 ? 4 : (CLS == 1 ? 2 : 1), WNW = 8 / WMW;
+    static_assert(CLS == 0 || CLS == 1, "two shape classes");
+    static constexpr int WMW = CLS == 0 ? 4 : 2, WNW = 8 / WMW;
     static constexpr int MB = 2, NQ = 4;                                    // 32-row / 32-column blocks per wavefront
     static constexpr int BMc = 32 * MB * WMW, BNc = 32 * NQ * WNW;
     static constexpr int U = BNc / 256;                                     // column units per tile
@@ -484,15 +514,13 @@ template <int CLS> struct Cls {
     static constexpr int RPC = 8192 / ROWB;                                 // slab rows one copy of the workgroup deposits
     static constexpr int A_BYTES = BMc * ROWB, B_BYTES = BNc * ROWB, SLAB = A_BYTES + B_BYTES;
     static constexpr int NSS = CLS == 1 ? 3 : 2;                            // slabs resident in LDS
-    static constexpr int CA = BMc >= RPC ? BMc / RPC : 1;                   // class 2: only wavefronts 0..3 copy the 64 A rows
-    static constexpr int CB = BNc / RPC, NCOPY = CA + CB;                   // copies per wavefront and slab
-    static constexpr bool A_HALF = BMc < RPC;
+    static constexpr int CA = BMc / RPC, CB = BNc / RPC, NCOPY = CA + CB;   // copies per wavefront and slab
     // copies per slot (slot 0, 1, 2; none later)
-    static constexpr int S0 = CLS == 0 ? 4 : (CLS == 1 ? 3 : NCOPY), S1 = CLS == 0 ? 4 : (CLS == 1 ? 2 : 0), S2 = 0;
+    static constexpr int S0 = CLS == 0 ? 4 : 3, S1 = CLS == 0 ? 4 : 2, S2 = 0;
     static_assert(S0 + S1 + S2 == NCOPY && (S2 == 0 || SUB > 2) && (S1 == 0 || SUB > 1), "the slots hold every copy and end before the next slab's last K step");
 };
-constexpr int ADAPTIVE_LDS = 139264;                          // 2 x 68 KiB (class 2) >= 2 x 64 KiB, 3 x 40 KiB
-constexpr int STAGE_OFF = 69632;                              // output staging (8 wavefronts x 8 KiB) sits above any class's slab 0
+constexpr int ADAPTIVE_LDS = 131072;                          // 2 x 64 KiB >= 3 x 40 KiB
+constexpr int STAGE_OFF = 65536;                              // output staging (8 wavefronts x 8 KiB) sits above either class's slab 0
 static_assert(STAGE_OFF + 8 * 8192 <= ADAPTIVE_LDS, "staging area inside the allocation");
 
 template <int PHASE>
@@ -597,8 +625,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
         unsigned char* base = smem + sbuf * C::SLAB + wave_bytes;
         const int koff = s * C::ROWB;                           // (plain locals: the builtin's operands must not be dependent expressions)
         if (n < C::CA) {
-            if (!C::A_HALF || wave < 4)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
                                                          a_voff[n], koff, 0, 0);
         } else {
             const int j = n - C::CA;
@@ -623,8 +650,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
     // Addresses of the tile and its slab 0 (buffer 0).  The other buffers may still stage the previous tile's output.
     auto start_tile = [&](int nt_, int cls) __attribute__((always_inline)) {
         if (cls == 0)      { setup(std::integral_constant<int, 0>{}, nt_); prologue(std::integral_constant<int, 0>{}, 0, 1); }
-        else if (cls == 1) { setup(std::integral_constant<int, 1>{}, nt_); prologue(std::integral_constant<int, 1>{}, 0, 1); }
-        else               { setup(std::integral_constant<int, 2>{}, nt_); prologue(std::integral_constant<int, 2>{}, 0, 1); }
+        else               { setup(std::integral_constant<int, 1>{}, nt_); prologue(std::integral_constant<int, 1>{}, 0, 1); }
     };
 
     // One tile of the class given by `tag`; its slab 0 is in flight (the other buffers may hold the previous tile's
@@ -634,7 +660,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
         typedef Cls<decltype(tag)::value> C;
         constexpr int MB = C::MB, NQ = C::NQ, NSS = C::NSS, SUB = C::SUB;
         constexpr int ROWB = C::ROWB, NMF = MB * NQ, NR = MB + NQ;
-        constexpr int LPS = C::NCOPY - (C::A_HALF ? 1 : 0);             // copies every wavefront issues per slab
+        constexpr int LPS = C::NCOPY;                                   // copies every wavefront issues per slab
         constexpr int NSTORE = MB * (PHASE == 1 ? 4 : 8);               // 1 KiB stores per wavefront and tile
         static_assert(NSS * C::NCOPY < 64 && NSS * C::SLAB <= ADAPTIVE_LDS && C::SLAB <= STAGE_OFF, "pipeline shape");
         const int NS = K / (ROWB / 2);
@@ -852,8 +878,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
     start_tile(__builtin_amdgcn_readfirstlane(s_ticket[1]), cls);
     while (cls >= 0) {
         if (cls == 0)      cls = run_tile(std::integral_constant<int, 0>{});
-        else if (cls == 1) cls = run_tile(std::integral_constant<int, 1>{});
-        else               cls = run_tile(std::integral_constant<int, 2>{});
+        else               cls = run_tile(std::integral_constant<int, 1>{});
     }
 }
 
