@@ -57,7 +57,10 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
                      const int32_t* __restrict__ traffic, const uint8_t* __restrict__ perms,
                      const int32_t* __restrict__ durations, const int32_t* __restrict__ count_ptr, int kmax,
                      int32_t* __restrict__ sizes, int2* __restrict__ win_ws, int32_t* __restrict__ wcnt_ws,
-                     int32_t* __restrict__ res_cnt, int32_t* __restrict__ wcount) {
+                     int32_t* __restrict__ res_cnt, int32_t* __restrict__ wcount, int32_t* __restrict__ src_sizes) {
+    // src_sizes (or null): [N][(kmax+2)*e_loc], this source's own count for every (slice, expert), written in full --
+    // then `sizes` is not touched, nothing has to be zeroed beforehand and no global atomic is needed (requires
+    // (kmax+1)*e_loc <= CNT_CAP, so that the counters of every source are in LDS)
     // wcnt_ws / res_cnt / wcount (all or none; only with (kmax+1)*e_loc <= CNT_CAP): per source the counts per
     // (window, expert), the counts of what was not shipped, and the number of windows -- what st_place_kernel needs
     __shared__ ScanSmem sm;
@@ -137,12 +140,34 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
             if (tid < e_loc) res_cnt[(size_t)s * e_loc + tid] = s == r ? 0 : lds_cnt[W * e_loc + tid];
             if (tid == 0) wcount[s] = W;
         }
-        for (int x = tid; x < (W + 1) * e_loc; x += ST_THREADS) {
-            int c = lds_cnt[x];
-            if (c == 0) continue;
-            int w = x / e_loc, el = x - w * e_loc;
-            int slice = s == r ? 0 : (w < W ? (win_in_lds ? lds_win[w].x : my_ws[w].x) : kmax + 1);
-            atomicAdd(&sizes[(size_t)slice * e_loc + el], c);
+        if (src_sizes) {
+            const int G = (kmax + 2) * e_loc;
+            for (int x = tid; x < G; x += ST_THREADS) {
+                const int slice = x / e_loc, el = x - slice * e_loc;
+                int w = -1;                                     // window of this source that feeds the slice, if any
+                if (s == r) {
+                    w = slice == 0 ? 0 : -1;
+                } else if (slice == kmax + 1) {
+                    w = W;
+                } else if (slice >= 1) {                        // windows are listed by ascending slice id
+                    int lo = 0, hi = W;
+                    while (lo < hi) {
+                        int mid = (lo + hi) >> 1;
+                        int id = win_in_lds ? lds_win[mid].x : my_ws[mid].x;
+                        if (id < slice) lo = mid + 1; else hi = mid;
+                    }
+                    if (lo < W && (win_in_lds ? lds_win[lo].x : my_ws[lo].x) == slice) w = lo;
+                }
+                src_sizes[(size_t)s * G + x] = w >= 0 ? lds_cnt[w * e_loc + el] : 0;
+            }
+        } else {
+            for (int x = tid; x < (W + 1) * e_loc; x += ST_THREADS) {
+                int c = lds_cnt[x];
+                if (c == 0) continue;
+                int w = x / e_loc, el = x - w * e_loc;
+                int slice = s == r ? 0 : (w < W ? (win_in_lds ? lds_win[w].x : my_ws[w].x) : kmax + 1);
+                atomicAdd(&sizes[(size_t)slice * e_loc + el], c);
+            }
         }
     }
 }
@@ -242,14 +267,22 @@ void st_place_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
 
 // offsets[0] = 0, offsets[g+1] = sizes[0] + ... + sizes[g]; one workgroup.
 __global__ __launch_bounds__(ST_THREADS)
-void st_scan_kernel(const int32_t* __restrict__ sizes, int G, int32_t* __restrict__ offsets) {
+void st_scan_kernel(const int32_t* __restrict__ sizes, int G, int32_t* __restrict__ offsets, const int32_t* __restrict__ src_sizes, int N) {
+    // src_sizes != null: the size of group g is the sum of the N sources' own counts
     __shared__ ScanSmem sm;
     const int tid = threadIdx.x;
     unsigned long long base = 0;
     if (tid == 0) offsets[0] = 0;
     for (int g0 = 0; g0 < G; g0 += ST_THREADS) {
         int g = g0 + tid;
-        unsigned long long v = g < G ? (unsigned long long)sizes[g] : 0ULL;
+        unsigned long long v = 0ULL;
+        if (g < G) {
+            if (src_sizes) {
+                for (int q = 0; q < N; ++q) v += (unsigned long long)src_sizes[(size_t)q * G + g];
+            } else {
+                v = (unsigned long long)sizes[g];
+            }
+        }
         int excl, tot;
         unsigned long long incl, stot;
         block_scan(sm, false, v, tid, excl, incl, tot, stot);
@@ -262,6 +295,16 @@ size_t sizes_bytes(int kmax, int e_loc) {
     size_t b = ((size_t)(kmax + 2) * e_loc) * sizeof(int32_t);
     return (b + 255) & ~(size_t)255;
 }
+
+// per-source sizes are used (and the zeroing kernel skipped) when every source's counters fit LDS and the table is small
+bool dense_sizes(int N, int kmax, int e_loc) {
+    return (long long)(kmax + 1) * e_loc <= CNT_CAP && (long long)N * (kmax + 2) * e_loc <= 65536;
+}
+size_t src_sizes_bytes(int N, int kmax, int e_loc) {
+    return dense_sizes(N, kmax, e_loc) ? (((size_t)N * (kmax + 2) * e_loc * sizeof(int32_t)) + 255) & ~(size_t)255 : 0;
+}
+
+size_t win_bytes(int N, int kmax) { return (((size_t)N * (kmax > 0 ? kmax : 1) * sizeof(int2)) + 255) & ~(size_t)255; }
 
 size_t rows_extra_bytes(int N, int kmax, int e_loc) {
     return ((size_t)N * (kmax + 1) * e_loc + (size_t)N * e_loc + (size_t)N) * sizeof(int32_t);
@@ -286,13 +329,15 @@ moe_status slice_table_impl(const int32_t* ids, int N, int T, int topk, int E, i
     hipStream_t s = (hipStream_t)hip_stream;
     int32_t* sizes = (int32_t*)workspace;
     int2* win_ws = (int2*)((char*)workspace + sizes_bytes(kmax, e_loc));
+    int32_t* src_sizes = dense_sizes(N, kmax, e_loc)
+                             ? (int32_t*)((char*)workspace + sizes_bytes(kmax, e_loc) + win_bytes(N, kmax)) : nullptr;
     int32_t *wcnt_ws = nullptr, *res_cnt = nullptr, *wcount = nullptr;
     if (want_rows) {
         wcnt_ws = (int32_t*)((char*)workspace + moe_slice_table_workspace_bytes(N, kmax, E));
         res_cnt = wcnt_ws + (size_t)N * (kmax + 1) * e_loc;
         wcount = res_cnt + (size_t)N * e_loc;
     }
-    {
+    if (!src_sizes) {
         moe::LaunchScope k("st_zero_kernel", s);
         int blocks = (int)((G + 255) / 256);
         if (blocks > 256) blocks = 256;
@@ -303,13 +348,13 @@ moe_status slice_table_impl(const int32_t* ids, int N, int T, int topk, int E, i
     {
         moe::LaunchScope k("st_count_kernel", s);
         hipLaunchKernelGGL(st_count_kernel, dim3(N), dim3(ST_THREADS), 0, s, ids, N, (int)per_src, E, e_loc, r, traffic,
-                           perms, durations, count, kmax, sizes, win_ws, wcnt_ws, res_cnt, wcount);
+                           perms, durations, count, kmax, sizes, win_ws, wcnt_ws, res_cnt, wcount, src_sizes);
         moe_status st = k.done();
         if (st != MOE_OK) return st;
     }
     {
         moe::LaunchScope k("st_scan_kernel", s);
-        hipLaunchKernelGGL(st_scan_kernel, dim3(1), dim3(ST_THREADS), 0, s, sizes, (int)G, offsets);
+        hipLaunchKernelGGL(st_scan_kernel, dim3(1), dim3(ST_THREADS), 0, s, sizes, (int)G, offsets, src_sizes, N);
         moe_status st = k.done();
         if (st != MOE_OK || !want_rows) return st;
     }
@@ -323,7 +368,7 @@ moe_status slice_table_impl(const int32_t* ids, int N, int T, int topk, int E, i
 
 extern "C" size_t moe_slice_table_workspace_bytes(int N, int kmax, int E) {
     if (N < 1 || kmax < 0 || E < 1 || E % N != 0) return 0;
-    return sizes_bytes(kmax, E / N) + (size_t)N * (kmax > 0 ? kmax : 1) * sizeof(int2);
+    return sizes_bytes(kmax, E / N) + win_bytes(N, kmax) + src_sizes_bytes(N, kmax, E / N);
 }
 
 extern "C" size_t moe_slice_table_rows_workspace_bytes(int N, int kmax, int E) {
