@@ -519,15 +519,18 @@ template <int CLS> struct Cls {
     static constexpr int S0 = CLS == 0 ? 4 : 3, S1 = CLS == 0 ? 4 : 2, S2 = 0;
     static_assert(S0 + S1 + S2 == NCOPY && (S2 == 0 || SUB > 2) && (S1 == 0 || SUB > 1), "the slots hold every copy and end before the next slab's last K step");
 };
-constexpr int ADAPTIVE_LDS = 131072;                          // 2 x 64 KiB >= 3 x 40 KiB
-constexpr int STAGE_OFF = 65536;                              // output staging (8 wavefronts x 8 KiB) sits above either class's slab 0
-static_assert(STAGE_OFF + 8 * 8192 <= ADAPTIVE_LDS, "staging area inside the allocation");
+constexpr int STAGE_OFF = 131072;                             // slab buffers below (2 x 64 KiB >= 3 x 40 KiB), output staging above
+constexpr int STAGE_WAVE = 4096;                              // staging per wavefront: 32 rows x 128 bytes
+constexpr int ADAPTIVE_LDS = STAGE_OFF + 8 * STAGE_WAVE;      // 160 KiB: all of a compute unit's LDS
 
 template <int PHASE>
 __global__ __launch_bounds__(512, 1)
 void ffn_adaptive_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ int s_ticket[6];                        // next tile: (block, tile index, class, first row, end row, expert); block -1 = none
+    // next tile: (block, tile index, class, first row, end row, expert); block -1 = none.  It shares its bytes with
+    // wavefront 0's output staging: written by that wavefront after its read-out, read by the others before the
+    // next read-out begins (inside the slab loop, or ahead of a barrier).
+    int* const s_ticket = reinterpret_cast<int*>(smem + STAGE_OFF);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -555,18 +558,27 @@ void ffn_adaptive_kernel(FfnArgs a) {
     // thread 0 pulls tickets (own queue first, then the others).  A ticket names (block, unit); it is a tile only if
     // the unit is the first of the tile its block's class makes of it.
     auto fetch = [&](int first_k) __attribute__((always_inline)) {
-        int q = my_xcd, k = first_k, blk = -1, unit = -1, cls = 0;
+        int q = my_xcd, blk = -1, unit = -1, cls = 0;
         int4 info = make_int4(0, 0, 0, 0);
-        for (int tries = 0; tries < 8;) {
-            int st = geom.decode(q, k, blk, unit);
-            if (st == 1) {
-                info = a.plan[PLAN_HDR + blk];
-                cls = info.w;
-                if ((unit & ((1 << cls) - 1)) == 0) break;
-            }
-            if (st < 0) { ++tries; q = (q + 1) & 7; }
+        // 1 = a tile, 0 = no tile behind this ticket, -1 = queue exhausted
+        auto look = [&](int k) __attribute__((always_inline)) -> int {
+            const int st = geom.decode(q, k, blk, unit);
+            if (st != 1) { blk = -1; return st; }
+            // (a scalar load: the plan is read-only here, and a vector load's return would be counted behind the
+            //  slab copies in flight)
+            const __attribute__((address_space(4))) int* entry =
+                (const __attribute__((address_space(4))) int*)a.plan + 4 * (PLAN_HDR + __builtin_amdgcn_readfirstlane(blk));
+            info = make_int4(entry[0], entry[1], entry[2], entry[3]);
+            cls = info.w;
+            if ((unit & ((1 << cls) - 1)) == 0) return 1;
             blk = -1;
-            if (tries < 8) k = atomicAdd(&queues[q], 1);
+            return 0;
+        };
+        // the first look stands outside the loop: the wait for first_k then counts the copies issued since
+        int st = look(first_k);
+        for (int tries = 0; st != 1;) {
+            if (st < 0) { if (++tries == 8) break; q = (q + 1) & 7; }
+            st = look(atomicAdd(&queues[q], 1));
         }
         s_ticket[0] = blk; s_ticket[1] = blk >= 0 ? (unit >> cls) : 0; s_ticket[2] = cls;
         s_ticket[3] = info.x; s_ticket[4] = info.y; s_ticket[5] = info.z;      // the plan entry travels with the ticket
@@ -647,22 +659,23 @@ void ffn_adaptive_kernel(FfnArgs a) {
                 for (int n = 0; n < C::NCOPY; ++n) issue_copy(tag, s, s, n);
             }
     };
-    // Addresses of the tile and its slab 0 (buffer 0).  The other buffers may still stage the previous tile's output.
+    // Addresses of the tile and its first slabs, one per buffer (every K here has more slabs than there are buffers).
     auto start_tile = [&](int nt_, int cls) __attribute__((always_inline)) {
-        if (cls == 0)      { setup(std::integral_constant<int, 0>{}, nt_); prologue(std::integral_constant<int, 0>{}, 0, 1); }
-        else               { setup(std::integral_constant<int, 1>{}, nt_); prologue(std::integral_constant<int, 1>{}, 0, 1); }
+        if (cls == 0)      { setup(std::integral_constant<int, 0>{}, nt_); prologue(std::integral_constant<int, 0>{}, 0, 2); }
+        else               { setup(std::integral_constant<int, 1>{}, nt_); prologue(std::integral_constant<int, 1>{}, 0, 3); }
     };
 
-    // One tile of the class given by `tag`; its slab 0 is in flight (the other buffers may hold the previous tile's
-    // output staging and are filled after the opening barrier).  Returns the class of the next tile (whose slab 0 it
-    // has issued in its last slabs or before its own read-out) or -1.
+    // One tile of the class given by `tag`; its first slabs (one per buffer) are in flight.  Returns the class of the
+    // next tile (whose first slabs it has issued: slab 0 in its last slabs or before its own read-out, the others
+    // before the read-out) or -1.
     auto run_tile = [&](auto tag) __attribute__((always_inline)) -> int {
         typedef Cls<decltype(tag)::value> C;
         constexpr int MB = C::MB, NQ = C::NQ, NSS = C::NSS, SUB = C::SUB;
         constexpr int ROWB = C::ROWB, NMF = MB * NQ, NR = MB + NQ;
         constexpr int LPS = C::NCOPY;                                   // copies every wavefront issues per slab
         constexpr int NSTORE = MB * (PHASE == 1 ? 4 : 8);               // 1 KiB stores per wavefront and tile
-        static_assert(NSS * C::NCOPY < 64 && NSS * C::SLAB <= ADAPTIVE_LDS && C::SLAB <= STAGE_OFF, "pipeline shape");
+        static_assert((NSS - 1) * C::NCOPY + NSTORE < 64 && NSS * C::SLAB <= STAGE_OFF, "pipeline shape");
+        static_assert(Cls<0>::MB == Cls<1>::MB, "a tile of either class issues NSTORE output stores");
         const int NS = K / (ROWB / 2);
         const int wm = wave / C::WNW, wn = wave % C::WNW;
         const int b_wave_row = PHASE == 1 ? (wn >> 1) * 256 + (wn & 1) * 64 : wn * 128;
@@ -690,12 +703,15 @@ void ffn_adaptive_kernel(FfnArgs a) {
         int nblk = -1, nnt = 0, ncls = 0;                                // ticket of the next tile
         bool chained = false;                                            // the next tile's slab 0 was issued inside this tile
 
-        // slab 0 went out before the previous tile's output stores, whose completion need not be awaited when their
-        // number is known (memory operations of a wavefront are counted in order)
-        if (counted_stores) wait_vmcnt<NSTORE>(); else wait_vmcnt<0>();
-        lds_barrier();                   // slab 0 is in LDS; nobody reads the output staging area or this tile's ticket any more
-        prologue(tag, 1, NSS);
-        if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));             // ticket of the next tile
+        // Issued so far, oldest first: slab 0, the slabs of the other buffers, the previous tile's output stores.  The
+        // stores need not be awaited when their number is known (memory operations of a wavefront are counted in order).
+        if (counted_stores) wait_vmcnt<(NSS - 1) * LPS + NSTORE>(); else wait_vmcnt<(NSS - 1) * LPS>();
+        lds_barrier();                   // slab 0 is in LDS
+        // Ticket of the next tile: the counter's old value returns while slab 0 is multiplied and is turned into a
+        // ticket after that slab (waiting for it here would hold wavefront 0, and with it every barrier, until the
+        // copies just issued have landed: memory operations of a wavefront return in order).
+        int next_k = 0;
+        if (tid == 0) next_k = atomicAdd(&queues[my_xcd], 1);
         bf16x8 wf[2][NQ], xf[2][MB];
 #pragma unroll
         for (int i = 0; i < NR; ++i) load_frag_one(wf[0], xf[0], 0, 0, i);
@@ -761,6 +777,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
             if constexpr (decltype(tag)::value == 0) {
                 // 256-row class: K is a multiple of 128 and at least 256, so NS is even and >= 4; slab s sits in buffer s & 1
                 slab(0, 0, T, F, F, C0);
+                if (tid == 0) fetch(next_k);
                 int s = 1;
                 for (; s + 2 < NS; ++s) slab(s, s & 1, T, T, F, C0);
                 // a barrier has passed since the next tile's ticket was written
@@ -776,6 +793,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
                 auto next = [&]() __attribute__((always_inline)) { buf = buf + 1 == NSS ? 0 : buf + 1; };
                 if (NSS < NS) slab(0, 0, T, F, F, C0); else slab(0, 0, F, F, F, C0);        // (every K here has at least 2 slabs)
                 next();
+                if (tid == 0) fetch(next_k);
                 int s = 1;
                 for (; s + NSS < NS; ++s) { slab(s, buf, T, T, F, C0); next(); }
                 if (s + 1 < NS && s - 1 + NSS < NS) { slab(s, buf, F, T, F, C0); next(); ++s; }
@@ -784,27 +802,31 @@ void ffn_adaptive_kernel(FfnArgs a) {
             }
         }
         lds_barrier();                   // every fragment is in registers: all buffers are free; next ticket visible
-        if (!chained) {
+        if (chained) {
+            prologue(tag, 1, NSS);                                      // slab 0 is under way; the other buffers follow
+        } else {
             nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]); nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]);
             ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);         // uniform: keeps the copy descriptors in scalar registers
-            if (nblk >= 0) start_tile(nnt, ncls);                       // the next tile's first slab flies during the epilogue
+            if (nblk >= 0) start_tile(nnt, ncls);                       // the next tile's first slabs fly during the epilogue
+            lds_barrier();                                              // the ticket has been read: its bytes may stage output
         }
 
         // ---- epilogue.  acc[mb][q][v]: row l31 of row block mb; column 8*(v>>2) + 4*lhi + (v&3) of column block q.
         // A lane holds 4 consecutive columns of one row: stored from there, one instruction would touch 32 rows with
-        // 16 bytes each, and the L2 takes one request per piece.  Each wavefront instead passes its 32-row block through
-        // a private staging area in LDS (above slab 0 of the next tile, which is arriving) and stores whole 128-byte
-        // lines: 16-byte chunk c of row r sits at position c ^ swz(r), conflict-free both ways.
+        // 16 bytes each, and the L2 takes one request per piece.  Each wavefront instead passes 32 rows x 64 columns at
+        // a time through a private staging area in LDS (above the slab buffers, where the next tile is arriving) and
+        // stores whole 128-byte lines: 16-byte chunk c of row r sits at position c ^ swz(r), conflict-free both ways.
         const int ug = ent * C::U + (wn >> 1);
-        constexpr int SROW = PHASE == 1 ? 128 : 256;                       // staged bytes per row: 64 / 128 columns
+        constexpr int SROW = 128;                                           // staged bytes per row: 64 columns
         constexpr int CPR = SROW / 16;                                      // chunks per row
         constexpr int RPI = 64 / CPR;                                       // rows one store instruction covers
+        constexpr int NH = PHASE == 1 ? 1 : 2;                              // 64-column halves of the wavefront's output
         int lane_e = lane;
         asm volatile("" : "+v"(lane_e));                                    // address arithmetic stays here, not in registers held across the tile loop
         const int el31 = lane_e & 31, elhi = lane_e >> 5;
         const int sr = lane_e / CPR, sc = lane_e % CPR;
-        auto swz = [](int r) { return PHASE == 1 ? (r >> 1) & 7 : r & 15; };
-        unsigned char* stage = smem + STAGE_OFF + wave * (32 * SROW);
+        auto swz = [](int r) { return (r >> 1) & 7; };
+        unsigned char* stage = smem + STAGE_OFF + wave * STAGE_WAVE;
         unsigned char* wr = stage + el31 * SROW + elhi * 8;
         const int wrow = em0 + wm * 32 * MB;                                // first row of this wavefront
         const bool scatter = PHASE == 2 && (a.row_map || a.row_gate);
@@ -824,48 +846,44 @@ void ffn_adaptive_kernel(FfnArgs a) {
         if (!scatter || ug < NU) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                if (PHASE == 1) {
+                if (PHASE == 2 && scatter && a.row_gate) {                // router weight of the row
+                    float gate = 1.0f;
+                    if (wrow + mb * 32 + el31 < em_end) gate = a.row_gate[wrow + mb * 32 + el31];
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[mb][q][v] *= gate;
+                }
+#pragma unroll
+                for (int hq = 0; hq < NH; ++hq) {
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
 #pragma unroll
                         for (int vg = 0; vg < 4; ++vg) {
                             float hv[4];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) hv[j] = silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j];
+                            for (int j = 0; j < 4; ++j)
+                                hv[j] = PHASE == 1 ? silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j]
+                                                   : acc[mb][hq * 2 + q][vg * 4 + j];
                             *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) = pack4(hv[0], hv[1], hv[2], hv[3]);
                         }
-                } else {
-                    if (scatter && a.row_gate) {                          // router weight of the row
-                        float gate = 1.0f;
-                        if (wrow + mb * 32 + el31 < em_end) gate = a.row_gate[wrow + mb * 32 + el31];
-#pragma unroll
-                        for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) acc[mb][q][v] *= gate;
-                    }
-#pragma unroll
-                    for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                        for (int vg = 0; vg < 4; ++vg)
-                            *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) =
-                                pack4(acc[mb][q][vg * 4], acc[mb][q][vg * 4 + 1], acc[mb][q][vg * 4 + 2], acc[mb][q][vg * 4 + 3]);
-                }
-                u32x4 v[32 / RPI];
-#pragma unroll
-                for (int i = 0; i < 32 / RPI; ++i) {
-                    const int r = i * RPI + sr;
-                    v[i] = *reinterpret_cast<const u32x4*>(stage + r * SROW + ((sc ^ swz(r)) << 4));
-                }
-                if (!scatter) {
-#pragma unroll
-                    for (int i = 0; i < 32 / RPI; ++i)
-                        __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO, (mb * 32 + i * RPI + sr) * rowb + sc * 16, 0, 0);
-                } else {
+                    u32x4 v[32 / RPI];
 #pragma unroll
                     for (int i = 0; i < 32 / RPI; ++i) {
-                        const int m = wrow + mb * 32 + i * RPI + sr;
-                        if (m < em_end)
-                            *reinterpret_cast<u32x4*>(a.y + (long long)mapped_row(a, m) * a.d + ug * 256 + (wn & 1) * 128 + sc * 8) = v[i];
+                        const int r = i * RPI + sr;
+                        v[i] = *reinterpret_cast<const u32x4*>(stage + r * SROW + ((sc ^ swz(r)) << 4));
+                    }
+                    if (!scatter) {
+#pragma unroll
+                        for (int i = 0; i < 32 / RPI; ++i)
+                            __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO, (mb * 32 + i * RPI + sr) * rowb + hq * SROW + sc * 16, 0, 0);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 32 / RPI; ++i) {
+                            const int m = wrow + mb * 32 + i * RPI + sr;
+                            if (m < em_end)
+                                *reinterpret_cast<u32x4*>(a.y + (long long)mapped_row(a, m) * a.d + ug * 256 + (wn & 1) * 128 + hq * 64 + sc * 8) = v[i];
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
