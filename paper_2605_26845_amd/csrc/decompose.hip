@@ -223,25 +223,49 @@ __device__ __forceinline__ void build_masks(const T* R, int N, int lane, Mask<NP
 }
 
 // One level of the alternating breadth-first search used by both the lexicographic pass and
-// the BvN repair.  Rows satisfying `eligible` that touch a reached column become visited and
-// remember that column; returns the set of rows visited in this level.
-template <int NPL>
-__device__ __forceinline__ Mask<NPL> bfs_visit_rows(const Mask<NPL> (&tm)[NPL], const Mask<NPL>& reached, int N, int lane,
-                                                    int min_row_exclusive, bool (&visited)[NPL], int (&parent)[NPL]) {
+// the BvN repair.  Rows of `open` (those that may still be visited) that touch a reached column are visited,
+// leave `open` and remember that column; returns the set of rows visited in this level.  The sets of rows are
+// uniform masks: a per-lane flag carried around the search loop would live in a vector register and cost a
+// select and a compare per level.
+// SMALL (N <= 32, here and below): the masks fit 32 bits and the per-lane arithmetic on them is done in 32 bits
+// (64-bit shifts and compares run at a fraction of the 32-bit rate).
+template <int NPL, bool SMALL = false>
+__device__ __forceinline__ Mask<NPL> bfs_visit_rows(const Mask<NPL> (&tm)[NPL], const Mask<NPL>& reached, int lane,
+                                                    Mask<NPL>& open, int (&parent)[NPL]) {
     Mask<NPL> vm;
+    if constexpr (SMALL) {
+        static_assert(NPL == 1, "32-bit masks");
+        const unsigned int hit = (unsigned int)tm[0].w[0] & (unsigned int)reached.w[0];
+        vm.w[0] = ballot64(hit != 0) & open.w[0];
+        if (__builtin_amdgcn_inverse_ballot_w64(vm.w[0])) parent[0] = __builtin_ctz(hit);
+        open.w[0] &= ~vm.w[0];
+        return vm;
+    }
 #pragma unroll
     for (int s = 0; s < NPL; ++s) {
-        int row = lane + 64 * s;
         Mask<NPL> hit = tm[s] & reached;
-        bool nv = row > min_row_exclusive && row < N && !visited[s] && hit.any();
-        if (nv) { visited[s] = true; parent[s] = hit.first(); }
-        vm.w[s] = ballot64(nv);
+        vm.w[s] = ballot64(hit.any()) & open.w[s];
+        if (__builtin_amdgcn_inverse_ballot_w64(vm.w[s])) parent[s] = hit.first();
+        open.w[s] &= ~vm.w[s];
     }
     return vm;
 }
-// Columns whose current owner row is in `rows` join `reached`.
+// rows after row i (i = -1: all rows)
 template <int NPL>
+__device__ __forceinline__ Mask<NPL> rows_after(int i, int N) {
+    Mask<NPL> r = below<NPL>(N), b = below<NPL>(i + 1);
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) r.w[k] &= ~b.w[k];
+    return r;
+}
+// Columns whose current owner row is in `rows` join `reached`.
+template <int NPL, bool SMALL = false>
 __device__ __forceinline__ void bfs_reach_cols(const int (&p)[NPL], const Mask<NPL>& rows, int N, int lane, Mask<NPL>& reached) {
+    if constexpr (SMALL) {
+        const bool nr = lane < N && p[0] >= 0 && (((unsigned int)rows.w[0] >> (p[0] & 31)) & 1u);
+        reached.w[0] |= ballot64(nr);
+        return;
+    }
 #pragma unroll
     for (int s = 0; s < NPL; ++s) {
         int c = lane + 64 * s;
@@ -284,9 +308,17 @@ __device__ __forceinline__ unsigned long long wave_or_scan64(unsigned long long 
 
 // Rows >= first_row that have an allowed column below their current one which is not held by an earlier row.
 // Only those rows can possibly move to a smaller column; all others are skipped by the lexicographic pass.
-template <int NPL>
+template <int NPL, bool SMALL = false>
 __device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[NPL], int N, int lane, const int (&sigma)[NPL],
                                                           int first_row) {
+    if constexpr (SMALL) {
+        const unsigned int own = lane < N ? 1u << (sigma[0] & 31) : 0u;
+        const unsigned int taken = wave_or_scan32(own);                  // columns of rows up to and including this one
+        const bool want = lane < N && lane >= first_row && ((unsigned int)tm[0].w[0] & (own - 1u) & ~taken) != 0;
+        Mask<NPL> need;
+        need.w[0] = ballot64(want);
+        return need;
+    }
     // taken[s] = columns held by rows up to and including this lane's row (rows are a permutation: own bit removed below)
     Mask<NPL> taken[NPL], carry;
     carry.clear();
@@ -333,11 +365,11 @@ __device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[
 // and on row i's column; for i > last_row none of the three has changed, so such a row still cannot move and is not
 // examined.  A re-routing inside this pass raises last_row to the largest row it moved.  (Keeping track of last_row
 // costs a 16 x 16 decomposition more than the few searches it saves there; at 64 x 64 it saves a seventh of the time.)
-template <int NPL, bool BOUND = false>
+template <int NPL, bool BOUND = false, bool SMALL = false>
 __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, int lane, int (&sigma)[NPL], int (&p)[NPL],
                                              int first_row, int last_row = 0) {
     for (int round = 0; round <= N; ++round) {
-        Mask<NPL> need = rows_with_candidates<NPL>(tm, N, lane, sigma, first_row);
+        Mask<NPL> need = rows_with_candidates<NPL, SMALL>(tm, N, lane, sigma, first_row);
         if (BOUND) need = need & below<NPL>(last_row + 1);
         bool changed = false;
         while (need.any() && !changed) {
@@ -353,15 +385,15 @@ __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, 
             Mask<NPL> reached;
             reached.clear();
             reached.set(cur);
-            bool visited[NPL];
+            Mask<NPL> open = rows_after<NPL>(i, N);
             int parent[NPL];
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+            for (int s = 0; s < NPL; ++s) parent[s] = -1;
             const int best = cand.first();
             for (int level = 0; level < N; ++level) {
-                Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, i, visited, parent);
+                Mask<NPL> vm = bfs_visit_rows<NPL, SMALL>(tm, reached, lane, open, parent);
                 if (!vm.any()) break;
-                bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                bfs_reach_cols<NPL, SMALL>(p, vm, N, lane, reached);
                 if (reached.test(best)) break;
             }
             Mask<NPL> hit = cand & reached;
@@ -621,7 +653,7 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                 build_masks<NPL, T>(R, N, lane, tm, [&](int x, int i, int s) { return bcast<NPL>(u, i) + vv[s] == x; });
             }
         }
-        lex_smallest<NPL>(tm, N, lane, sigma, p, 0);
+        lex_smallest<NPL, false, NPL == 1 && NW <= 2>(tm, N, lane, sigma, p, 0);
         // ---- ship whole entries; the matching lasts as long as its heaviest pair
         int dmax = 0, pos = 0;
 #pragma unroll
@@ -646,7 +678,8 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
 }
 
 // ------------------------------------------------------------------------------ BvN kernel
-template <int NPL, bool BOUND>             // BOUND: the lexicographic pass stops at the last row the repair moved
+template <int NPL, bool BOUND>             // BOUND (N > 32): the lexicographic pass stops at the last row the repair moved;
+                                           // otherwise (N <= 32) the mask arithmetic is done in 32 bits
 __global__ __launch_bounds__(MOE_WAVE)
 void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
                 int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
@@ -731,17 +764,17 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
                 Mask<NPL> reached;
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) reached.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
-                bool visited[NPL];
+                Mask<NPL> open = rows_after<NPL>(i, N);
                 int parent[NPL];
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                for (int s = 0; s < NPL; ++s) parent[s] = -1;
                 const Mask<NPL> allowed = bcast_mask<NPL>(tm, i);
                 const int best = allowed.any() ? allowed.first() : -1;
                 for (int level = 0; level <= N; ++level) {
                     if (best >= 0 && reached.test(best)) break;
-                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, i, visited, parent);
+                    Mask<NPL> vm = bfs_visit_rows<NPL, !BOUND>(tm, reached, lane, open, parent);
                     if (!vm.any()) break;
-                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                    bfs_reach_cols<NPL, !BOUND>(p, vm, N, lane, reached);
                 }
                 Mask<NPL> hit = allowed & reached;
                 if (hit.any()) {
@@ -765,13 +798,13 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
                 Mask<NPL> reached;
                 reached.clear();
                 reached.set(cf);
-                bool visited[NPL];
+                Mask<NPL> open = rows_after<NPL>(-1, N);
                 int parent[NPL];
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                for (int s = 0; s < NPL; ++s) parent[s] = -1;
                 int target_row = -1;
                 for (int level = 0; level <= N; ++level) {
-                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, -1, visited, parent);
+                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, lane, open, parent);
                     if (!vm.any()) break;
                     Mask<NPL> um;                    // newly visited rows that are unmatched
 #pragma unroll
@@ -784,7 +817,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
             }
         }
         if (broken) break;
-        lex_smallest<NPL, BOUND>(tm, N, lane, sigma, p, first_row < N ? (restricted_ok ? first_row + 1 : 0) : N, last_row);
+        lex_smallest<NPL, BOUND, !BOUND>(tm, N, lane, sigma, p, first_row < N ? (restricted_ok ? first_row + 1 : 0) : N, last_row);
         // ---- coefficient = smallest entry on the matching; subtract it
         int x[NPL], lmin = INT_MAX;
 #pragma unroll
@@ -930,17 +963,17 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
                 Mask<NPL> reached;
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) reached.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
-                bool visited[NPL];
+                Mask<NPL> open = rows_after<NPL>(i, N);
                 int parent[NPL];
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                for (int s = 0; s < NPL; ++s) parent[s] = -1;
                 const Mask<NPL> allowed = bcast_mask<NPL>(tm, i);
                 const int best = allowed.any() ? allowed.first() : -1;
                 for (int level = 0; level <= N; ++level) {
                     if (best >= 0 && reached.test(best)) break;
-                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, i, visited, parent);
+                    Mask<NPL> vm = bfs_visit_rows<NPL, !BOUND>(tm, reached, lane, open, parent);
                     if (!vm.any()) break;
-                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                    bfs_reach_cols<NPL, !BOUND>(p, vm, N, lane, reached);
                 }
                 Mask<NPL> hit = allowed & reached;
                 if (hit.any()) {
@@ -963,13 +996,13 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
                 Mask<NPL> reached;
                 reached.clear();
                 reached.set(cf);
-                bool visited[NPL];
+                Mask<NPL> open = rows_after<NPL>(-1, N);
                 int parent[NPL];
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) { visited[s] = false; parent[s] = -1; }
+                for (int s = 0; s < NPL; ++s) parent[s] = -1;
                 int target_row = -1;
                 for (int level = 0; level <= N; ++level) {
-                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, N, lane, -1, visited, parent);
+                    Mask<NPL> vm = bfs_visit_rows<NPL>(tm, reached, lane, open, parent);
                     if (!vm.any()) break;
                     Mask<NPL> um;
 #pragma unroll
@@ -982,7 +1015,7 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
             }
         }
         if (stuck) break;
-        lex_smallest<NPL, BOUND>(tm, N, lane, sigma, p, first_row < N ? (restricted_ok ? first_row + 1 : 0) : N, last_row);
+        lex_smallest<NPL, BOUND, !BOUND>(tm, N, lane, sigma, p, first_row < N ? (restricted_ok ? first_row + 1 : 0) : N, last_row);
         double x[NPL], lmin = 1.0e300;
 #pragma unroll
         for (int s = 0; s < NPL; ++s) {
