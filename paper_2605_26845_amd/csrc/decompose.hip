@@ -75,7 +75,9 @@ __device__ __forceinline__ int wave_sum(int x) {
     return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
            __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
 }
-__device__ __forceinline__ unsigned long long ballot64(bool p) { return __ballot(p); }
+// (the builtin takes the predicate as a lane mask; __ballot() takes an int, for which a predicate that already is a
+//  lane mask goes through a vector register and a compare)
+__device__ __forceinline__ unsigned long long ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 // The workgroup is a single wavefront, whose LDS accesses execute in program order: no barrier is needed
 // between a lane's store and another lane's load, only that the compiler keeps that order and that pending
 // LDS traffic has drained.  (__syncthreads() would also wait for every outstanding global store.)
@@ -258,20 +260,18 @@ __device__ __forceinline__ Mask<NPL> rows_after(int i, int N) {
     for (int k = 0; k < NPL; ++k) r.w[k] &= ~b.w[k];
     return r;
 }
-// Columns whose current owner row is in `rows` join `reached`.
+// Columns whose current owner row is in `rows` join `reached`; `owned` = the columns that have an owner.
+// (Every ballot here is fed by a single comparison and the sets are combined as uniform masks: a conjunction of
+// per-lane conditions handed to a ballot is first turned into a 0/1 vector register and compared again.)
 template <int NPL, bool SMALL = false>
-__device__ __forceinline__ void bfs_reach_cols(const int (&p)[NPL], const Mask<NPL>& rows, int N, int lane, Mask<NPL>& reached) {
+__device__ __forceinline__ void bfs_reach_cols(const int (&p)[NPL], const Mask<NPL>& rows, const Mask<NPL>& owned, int lane,
+                                               Mask<NPL>& reached) {
     if constexpr (SMALL) {
-        const bool nr = lane < N && p[0] >= 0 && (((unsigned int)rows.w[0] >> (p[0] & 31)) & 1u);
-        reached.w[0] |= ballot64(nr);
+        reached.w[0] |= ballot64((((unsigned int)rows.w[0] >> (p[0] & 31)) & 1u) != 0) & owned.w[0];
         return;
     }
 #pragma unroll
-    for (int s = 0; s < NPL; ++s) {
-        int c = lane + 64 * s;
-        bool nr = c < N && p[s] >= 0 && rows.test(p[s]);
-        reached.w[s] |= ballot64(nr);
-    }
+    for (int s = 0; s < NPL; ++s) reached.w[s] |= ballot64(rows.test(p[s] & (64 * NPL - 1))) & owned.w[s];
 }
 // Re-route along the parents: `row` takes `col`, the previous owner of `col` takes its parent column, ...
 // until a column without an owner has been taken.  TOP: returns the largest row that changed its column (else 0).
@@ -314,9 +314,8 @@ __device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[
     if constexpr (SMALL) {
         const unsigned int own = lane < N ? 1u << (sigma[0] & 31) : 0u;
         const unsigned int taken = wave_or_scan32(own);                  // columns of rows up to and including this one
-        const bool want = lane < N && lane >= first_row && ((unsigned int)tm[0].w[0] & (own - 1u) & ~taken) != 0;
-        Mask<NPL> need;
-        need.w[0] = ballot64(want);
+        Mask<NPL> need = rows_after<NPL>(first_row - 1, N);
+        need.w[0] &= ballot64(((unsigned int)tm[0].w[0] & (own - 1u) & ~taken) != 0);
         return need;
     }
     // taken[s] = columns held by rows up to and including this lane's row (rows are a permutation: own bit removed below)
@@ -368,6 +367,7 @@ __device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[
 template <int NPL, bool BOUND = false, bool SMALL = false>
 __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, int lane, int (&sigma)[NPL], int (&p)[NPL],
                                              int first_row, int last_row = 0) {
+    const Mask<NPL> all = below<NPL>(N);                // every column has an owner here
     for (int round = 0; round <= N; ++round) {
         Mask<NPL> need = rows_with_candidates<NPL, SMALL>(tm, N, lane, sigma, first_row);
         if (BOUND) need = need & below<NPL>(last_row + 1);
@@ -379,7 +379,7 @@ __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, 
             // columns of rows < i are fixed
             Mask<NPL> cand = bcast_mask<NPL>(tm, i) & below<NPL>(cur);
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) cand.w[s] &= ~ballot64(lane + 64 * s < N && p[s] >= 0 && p[s] < i);
+            for (int s = 0; s < NPL; ++s) cand.w[s] &= ~(ballot64((unsigned int)p[s] < (unsigned int)i) & all.w[s]);
             if (!cand.any()) continue;
             // which columns can be vacated by re-routing rows > i, the column `cur` being free?
             Mask<NPL> reached;
@@ -393,7 +393,7 @@ __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, 
             for (int level = 0; level < N; ++level) {
                 Mask<NPL> vm = bfs_visit_rows<NPL, SMALL>(tm, reached, lane, open, parent);
                 if (!vm.any()) break;
-                bfs_reach_cols<NPL, SMALL>(p, vm, N, lane, reached);
+                bfs_reach_cols<NPL, SMALL>(p, vm, all, lane, reached);
                 if (reached.test(best)) break;
             }
             Mask<NPL> hit = cand & reached;
@@ -740,6 +740,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
     }
 
     int p[NPL], sigma[NPL];
+    const Mask<NPL> all = below<NPL>(N);             // the rows, or the columns, of the matrix
 #pragma unroll
     for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
     Fnv fnv{FNV_OFFSET};
@@ -756,14 +757,17 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
         {
             Mask<NPL> unmatched;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) unmatched.w[s] = ballot64(lane + 64 * s < N && sigma[s] < 0);
+            for (int s = 0; s < NPL; ++s) unmatched.w[s] = ballot64(sigma[s] < 0) & all.w[s];
             while (unmatched.any() && restricted_ok) {
                 const int i = unmatched.first();
                 unmatched.reset(i);
                 first_row = min(first_row, i);
-                Mask<NPL> reached;
+                Mask<NPL> reached, owned;
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) reached.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+                for (int s = 0; s < NPL; ++s) {
+                    reached.w[s] = ballot64(p[s] < 0) & all.w[s];
+                    owned.w[s] = all.w[s] & ~reached.w[s];
+                }
                 Mask<NPL> open = rows_after<NPL>(i, N);
                 int parent[NPL];
 #pragma unroll
@@ -774,7 +778,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
                     if (best >= 0 && reached.test(best)) break;
                     Mask<NPL> vm = bfs_visit_rows<NPL, !BOUND>(tm, reached, lane, open, parent);
                     if (!vm.any()) break;
-                    bfs_reach_cols<NPL, !BOUND>(p, vm, N, lane, reached);
+                    bfs_reach_cols<NPL, !BOUND>(p, vm, owned, lane, reached);
                 }
                 Mask<NPL> hit = allowed & reached;
                 if (hit.any()) {
@@ -791,14 +795,16 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
             last_row = N - 1;
             Mask<NPL> free_cols;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+            for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(p[s] < 0) & all.w[s];
             while (free_cols.any() && !broken) {
                 const int cf = free_cols.first();
                 free_cols.reset(cf);
                 Mask<NPL> reached;
                 reached.clear();
                 reached.set(cf);
-                Mask<NPL> open = rows_after<NPL>(-1, N);
+                Mask<NPL> open = all, owned;
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) owned.w[s] = all.w[s] & ~ballot64(p[s] < 0);
                 int parent[NPL];
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) parent[s] = -1;
@@ -810,7 +816,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
 #pragma unroll
                     for (int s = 0; s < NPL; ++s) um.w[s] = vm.w[s] & ballot64(sigma[s] < 0);
                     if (um.any()) { target_row = um.first(); break; }
-                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                    bfs_reach_cols<NPL>(p, vm, owned, lane, reached);
                 }
                 if (target_row < 0) { broken = true; break; }     // impossible for equal line sums
                 apply_path<NPL>(target_row, bcast<NPL>(parent, target_row), sigma, p, parent, lane, N);
@@ -943,6 +949,7 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
         nnz += wave_sum(c);
     }
     int p[NPL], sigma[NPL];
+    const Mask<NPL> all = below<NPL>(N);             // the rows, or the columns, of the matrix
 #pragma unroll
     for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
     uint8_t* perms_b = perms ? perms + (size_t)b * kmax * N : nullptr;
@@ -955,14 +962,17 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
         {
             Mask<NPL> unmatched;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) unmatched.w[s] = ballot64(lane + 64 * s < N && sigma[s] < 0);
+            for (int s = 0; s < NPL; ++s) unmatched.w[s] = ballot64(sigma[s] < 0) & all.w[s];
             while (unmatched.any() && restricted_ok) {
                 const int i = unmatched.first();
                 unmatched.reset(i);
                 first_row = min(first_row, i);
-                Mask<NPL> reached;
+                Mask<NPL> reached, owned;
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) reached.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+                for (int s = 0; s < NPL; ++s) {
+                    reached.w[s] = ballot64(p[s] < 0) & all.w[s];
+                    owned.w[s] = all.w[s] & ~reached.w[s];
+                }
                 Mask<NPL> open = rows_after<NPL>(i, N);
                 int parent[NPL];
 #pragma unroll
@@ -973,7 +983,7 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
                     if (best >= 0 && reached.test(best)) break;
                     Mask<NPL> vm = bfs_visit_rows<NPL, !BOUND>(tm, reached, lane, open, parent);
                     if (!vm.any()) break;
-                    bfs_reach_cols<NPL, !BOUND>(p, vm, N, lane, reached);
+                    bfs_reach_cols<NPL, !BOUND>(p, vm, owned, lane, reached);
                 }
                 Mask<NPL> hit = allowed & reached;
                 if (hit.any()) {
@@ -989,14 +999,16 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
             last_row = N - 1;
             Mask<NPL> free_cols;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(lane + 64 * s < N && p[s] < 0);
+            for (int s = 0; s < NPL; ++s) free_cols.w[s] = ballot64(p[s] < 0) & all.w[s];
             while (free_cols.any() && !stuck) {
                 const int cf = free_cols.first();
                 free_cols.reset(cf);
                 Mask<NPL> reached;
                 reached.clear();
                 reached.set(cf);
-                Mask<NPL> open = rows_after<NPL>(-1, N);
+                Mask<NPL> open = all, owned;
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) owned.w[s] = all.w[s] & ~ballot64(p[s] < 0);
                 int parent[NPL];
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) parent[s] = -1;
@@ -1008,7 +1020,7 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
 #pragma unroll
                     for (int s = 0; s < NPL; ++s) um.w[s] = vm.w[s] & ballot64(sigma[s] < 0);
                     if (um.any()) { target_row = um.first(); break; }
-                    bfs_reach_cols<NPL>(p, vm, N, lane, reached);
+                    bfs_reach_cols<NPL>(p, vm, owned, lane, reached);
                 }
                 if (target_row < 0) { stuck = true; break; }      // the support holds no perfect matching: the scaling was approximate
                 apply_path<NPL>(target_row, bcast<NPL>(parent, target_row), sigma, p, parent, lane, N);
