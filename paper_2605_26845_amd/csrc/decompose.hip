@@ -83,15 +83,18 @@ __device__ __forceinline__ unsigned long long ballot64(bool p) { return __builti
 // LDS traffic has drained.  (__syncthreads() would also wait for every outstanding global store.)
 __device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-// lane-distributed arrays: element idx lives in lane idx & 63, slot idx >> 6
+// lane-distributed arrays: element idx lives in lane idx & 63, slot idx >> 6 (one slot: 0 <= idx < 64, and an index
+// outside that range matches no lane in set_at)
 template <int NPL>
 __device__ __forceinline__ int bcast(const int (&a)[NPL], int idx) {
+    if constexpr (NPL == 1) return rdlane(a[0], idx);           // (the instruction takes the lane number modulo 64)
     int r = rdlane(a[0], idx & 63);
     if (NPL > 1) { int r1 = rdlane(a[NPL - 1], idx & 63); r = (idx >> 6) ? r1 : r; }
     return r;
 }
 template <int NPL>
 __device__ __forceinline__ void set_at(int (&a)[NPL], int idx, int val, int lane) {
+    if constexpr (NPL == 1) { if (lane == idx) a[0] = val; return; }
 #pragma unroll
     for (int s = 0; s < NPL; ++s)
         if (lane == (idx & 63) && s == (idx >> 6)) a[s] = val;
@@ -115,11 +118,13 @@ template <int NPL> struct Mask {
         if (NPL > 1) x = (i >> 6) ? w[NPL - 1] : x;
         return (x >> (i & 63)) & 1ULL;
     }
-    __device__ __forceinline__ void set(int i) {
+    __device__ __forceinline__ void set(int i) {          // 0 <= i < 64 * NPL
+        if constexpr (NPL == 1) { w[0] |= 1ULL << i; return; }
 #pragma unroll
         for (int k = 0; k < NPL; ++k) if (k == (i >> 6)) w[k] |= 1ULL << (i & 63);
     }
     __device__ __forceinline__ void reset(int i) {
+        if constexpr (NPL == 1) { w[0] &= ~(1ULL << i); return; }
 #pragma unroll
         for (int k = 0; k < NPL; ++k) if (k == (i >> 6)) w[k] &= ~(1ULL << (i & 63));
     }
@@ -137,10 +142,11 @@ __device__ __forceinline__ Mask<NPL> operator&(const Mask<NPL>& a, const Mask<NP
     for (int k = 0; k < NPL; ++k) r.w[k] = a.w[k] & b.w[k];
     return r;
 }
-// bits strictly below position i
-template <int NPL>
+// bits strictly below position i (SMALL: 0 <= i <= 32 is known)
+template <int NPL, bool SMALL = false>
 __device__ __forceinline__ Mask<NPL> below(int i) {
     Mask<NPL> r;
+    if constexpr (SMALL) { r.w[0] = (1ULL << i) - 1ULL; return r; }
 #pragma unroll
     for (int k = 0; k < NPL; ++k) {
         int rel = i - 64 * k;
@@ -253,9 +259,9 @@ __device__ __forceinline__ Mask<NPL> bfs_visit_rows(const Mask<NPL> (&tm)[NPL], 
     return vm;
 }
 // rows after row i (i = -1: all rows)
-template <int NPL>
+template <int NPL, bool SMALL = false>
 __device__ __forceinline__ Mask<NPL> rows_after(int i, int N) {
-    Mask<NPL> r = below<NPL>(N), b = below<NPL>(i + 1);
+    Mask<NPL> r = below<NPL, SMALL>(N), b = below<NPL, SMALL>(i + 1);
 #pragma unroll
     for (int k = 0; k < NPL; ++k) r.w[k] &= ~b.w[k];
     return r;
@@ -314,7 +320,7 @@ __device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[
     if constexpr (SMALL) {
         const unsigned int own = lane < N ? 1u << (sigma[0] & 31) : 0u;
         const unsigned int taken = wave_or_scan32(own);                  // columns of rows up to and including this one
-        Mask<NPL> need = rows_after<NPL>(first_row - 1, N);
+        Mask<NPL> need = rows_after<NPL, true>(first_row - 1, N);
         need.w[0] &= ballot64(((unsigned int)tm[0].w[0] & (own - 1u) & ~taken) != 0);
         return need;
     }
@@ -367,7 +373,7 @@ __device__ __forceinline__ Mask<NPL> rows_with_candidates(const Mask<NPL> (&tm)[
 template <int NPL, bool BOUND = false, bool SMALL = false>
 __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, int lane, int (&sigma)[NPL], int (&p)[NPL],
                                              int first_row, int last_row = 0) {
-    const Mask<NPL> all = below<NPL>(N);                // every column has an owner here
+    const Mask<NPL> all = below<NPL, SMALL>(N);         // every column has an owner here
     for (int round = 0; round <= N; ++round) {
         Mask<NPL> need = rows_with_candidates<NPL, SMALL>(tm, N, lane, sigma, first_row);
         if (BOUND) need = need & below<NPL>(last_row + 1);
@@ -377,7 +383,7 @@ __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, 
             need.reset(i);
             int cur = bcast<NPL>(sigma, i);
             // columns of rows < i are fixed
-            Mask<NPL> cand = bcast_mask<NPL>(tm, i) & below<NPL>(cur);
+            Mask<NPL> cand = bcast_mask<NPL>(tm, i) & below<NPL, SMALL>(cur);
 #pragma unroll
             for (int s = 0; s < NPL; ++s) cand.w[s] &= ~(ballot64((unsigned int)p[s] < (unsigned int)i) & all.w[s]);
             if (!cand.any()) continue;
@@ -385,7 +391,7 @@ __device__ __forceinline__ void lex_smallest(const Mask<NPL> (&tm)[NPL], int N, 
             Mask<NPL> reached;
             reached.clear();
             reached.set(cur);
-            Mask<NPL> open = rows_after<NPL>(i, N);
+            Mask<NPL> open = rows_after<NPL, SMALL>(i, N);
             int parent[NPL];
 #pragma unroll
             for (int s = 0; s < NPL; ++s) parent[s] = -1;
@@ -740,7 +746,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
     }
 
     int p[NPL], sigma[NPL];
-    const Mask<NPL> all = below<NPL>(N);             // the rows, or the columns, of the matrix
+    const Mask<NPL> all = below<NPL, !BOUND>(N);     // the rows, or the columns, of the matrix
 #pragma unroll
     for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
     Fnv fnv{FNV_OFFSET};
@@ -768,7 +774,7 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
                     reached.w[s] = ballot64(p[s] < 0) & all.w[s];
                     owned.w[s] = all.w[s] & ~reached.w[s];
                 }
-                Mask<NPL> open = rows_after<NPL>(i, N);
+                Mask<NPL> open = rows_after<NPL, !BOUND>(i, N);
                 int parent[NPL];
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) parent[s] = -1;
@@ -949,7 +955,7 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
         nnz += wave_sum(c);
     }
     int p[NPL], sigma[NPL];
-    const Mask<NPL> all = below<NPL>(N);             // the rows, or the columns, of the matrix
+    const Mask<NPL> all = below<NPL, !BOUND>(N);     // the rows, or the columns, of the matrix
 #pragma unroll
     for (int s = 0; s < NPL; ++s) { p[s] = -1; sigma[s] = -1; }
     uint8_t* perms_b = perms ? perms + (size_t)b * kmax * N : nullptr;
@@ -973,7 +979,7 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
                     reached.w[s] = ballot64(p[s] < 0) & all.w[s];
                     owned.w[s] = all.w[s] & ~reached.w[s];
                 }
-                Mask<NPL> open = rows_after<NPL>(i, N);
+                Mask<NPL> open = rows_after<NPL, !BOUND>(i, N);
                 int parent[NPL];
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) parent[s] = -1;
