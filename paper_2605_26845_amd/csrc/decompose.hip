@@ -29,17 +29,6 @@ template <int CTRL>
 __device__ __forceinline__ int dpp(int v) {
     return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
 }
-// All 64 lanes must be active.
-__device__ __forceinline__ int wave_min(int x) {
-    x = min(x, dpp<0xB1>(x));    // quad_perm [1,0,3,2]
-    x = min(x, dpp<0x4E>(x));    // quad_perm [2,3,0,1]
-    x = min(x, dpp<0x141>(x));   // row_half_mirror
-    x = min(x, dpp<0x140>(x));   // row_mirror: every lane of a 16-lane row now holds the row's min
-    int a = __builtin_amdgcn_readlane(x, 0), b = __builtin_amdgcn_readlane(x, 16);
-    int c = __builtin_amdgcn_readlane(x, 32), d = __builtin_amdgcn_readlane(x, 48);
-    return min(min(a, b), min(c, d));
-}
-__device__ __forceinline__ int wave_max(int x) { return -wave_min(-x); }      // callers pass x > INT_MIN
 // Minimum over the first 16 * NW lanes (NW = 1, 2, 4); the reduction inside a 16-lane row folds into the min instruction.
 template <int CTRL>
 __device__ __forceinline__ int min_dpp(int x) { return min(x, __builtin_amdgcn_mov_dpp(x, CTRL, 0xF, 0xF, true)); }
@@ -58,15 +47,18 @@ __device__ __forceinline__ int wave_max_rows(int x) {
 }
 template <int NW>
 __device__ __forceinline__ int wave_min_rows(int x) {
-    x = min_dpp<0xB1>(x);
-    x = min_dpp<0x4E>(x);
-    x = min_dpp<0x141>(x);
-    x = min_dpp<0x140>(x);
+    x = min_dpp<0xB1>(x);        // quad_perm [1,0,3,2]
+    x = min_dpp<0x4E>(x);        // quad_perm [2,3,0,1]
+    x = min_dpp<0x141>(x);       // row_half_mirror
+    x = min_dpp<0x140>(x);       // row_mirror: every lane of a 16-lane row now holds the row's min
     int m = __builtin_amdgcn_readlane(x, 0);
     if (NW > 1) m = min(m, __builtin_amdgcn_readlane(x, 16));
     if (NW > 2) m = min(min(m, __builtin_amdgcn_readlane(x, 32)), __builtin_amdgcn_readlane(x, 48));
     return m;
 }
+// All 64 lanes must be active.
+__device__ __forceinline__ int wave_min(int x) { return wave_min_rows<4>(x); }
+__device__ __forceinline__ int wave_max(int x) { return wave_max_rows<4>(x); }
 __device__ __forceinline__ int wave_sum(int x) {
     x += dpp<0xB1>(x);
     x += dpp<0x4E>(x);
@@ -838,26 +830,31 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
             x[s] = i < N ? R[i * N + sigma[s]] : INT_MAX;
             lmin = min(lmin, x[s]);
         }
-        const int lambda = wave_min(lmin);
+        const int lambda = BOUND ? wave_min(lmin) : wave_min_rows<2>(lmin);      // (N <= 32: two 16-lane rows)
         emit_matching<NPL>(sigma, lambda, N, lane, t, perms_b, dur_b, hashes ? &fnv : nullptr);
         ++t;
+        // entries equal to the coefficient die (lanes without a row hold INT_MAX, which no coefficient reaches)
         Mask<NPL> dead_rows;
 #pragma unroll
         for (int s = 0; s < NPL; ++s) {
-            int i = lane + 64 * s;
-            bool dead = false;
-            if (i < N) {
-                int nx = x[s] - lambda;
-                R[i * N + sigma[s]] = nx;
-                dead = nx == 0;
-            }
-            if (dead) { tm[s].reset(sigma[s]); sigma[s] = -1; }
+            const int i = lane + 64 * s;
+            const bool dead = x[s] == lambda;
             dead_rows.w[s] = ballot64(dead);
+            if (i < N) R[i * N + sigma[s]] = x[s] - lambda;
+            if (dead) {
+                if constexpr (!BOUND) tm[s].w[0] = (unsigned int)tm[s].w[0] & ~(1u << (sigma[s] & 31));
+                else tm[s].reset(sigma[s]);
+                sigma[s] = -1;
+            }
         }
 #pragma unroll
         for (int s = 0; s < NPL; ++s) {
             nnz -= __popcll(dead_rows.w[s]);
-            if (p[s] >= 0 && dead_rows.test(p[s])) p[s] = -1;
+            // (a column without an owner tests some bit and, if that is set, becomes ownerless once more)
+            bool lost;
+            if constexpr (!BOUND) lost = (((unsigned int)dead_rows.w[0] >> (p[s] & 31)) & 1u) != 0;
+            else lost = dead_rows.test(p[s] & (64 * NPL - 1));
+            if (lost) p[s] = -1;
         }
         lds_fence();
     }
