@@ -207,14 +207,14 @@ template <int NPL, typename T, typename Pred>
 __device__ __forceinline__ void build_masks(const T* R, int N, int lane, Mask<NPL> (&tm)[NPL], Pred pred) {
 #pragma unroll
     for (int s = 0; s < NPL; ++s) tm[s].clear();
+    const Mask<NPL> cols = below<NPL>(N);
 #pragma unroll 4
     for (int i = 0; i < N; ++i) {
         Mask<NPL> row;
 #pragma unroll
         for (int s = 0; s < NPL; ++s) {
             int j = lane + 64 * s;
-            bool on = (j < N) && pred(R[i * N + (j < N ? j : 0)], i, s);
-            row.w[s] = ballot64(on);
+            row.w[s] = ballot64(pred(R[i * N + (j < N ? j : 0)], i, s)) & cols.w[s];
         }
 #pragma unroll
         for (int s = 0; s < NPL; ++s)

@@ -9,6 +9,7 @@ namespace {
 
 constexpr int ST_THREADS = 1024;
 constexpr int ST_WAVES = ST_THREADS / MOE_WAVE;
+constexpr int ST_ITEMS = 8;         // assignments one thread takes per pass of the walk
 constexpr int WIN_CAP = 2048;      // windows of one source kept in LDS (more spill to the workspace)
 constexpr int CNT_CAP = 8192;      // (window, expert) counters of one source kept in LDS
 
@@ -48,6 +49,29 @@ __device__ __forceinline__ void block_scan(ScanSmem& sm, bool flag, unsigned lon
     total_sum = stot;
 }
 
+// Block-wide exclusive scan of a small per-thread count, in thread order; `total` is the block total.  Two barriers.
+__device__ __forceinline__ void block_scan_counts(ScanSmem& sm, int cnt, int tid, int& excl, int& total) {
+    const int lane = tid & 63, wave = tid >> 6;
+    int run = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(run, off);
+        if (lane >= off) run += o;
+    }
+    if (lane == 63) sm.wave_cnt[wave] = run;
+    __syncthreads();
+    int cbase = 0, ctot = 0;
+#pragma unroll
+    for (int w = 0; w < ST_WAVES; ++w) {
+        int c = sm.wave_cnt[w];
+        if (w < wave) cbase += c;
+        ctot += c;
+    }
+    __syncthreads();
+    excl = cbase + run - cnt;
+    total = ctot;
+}
+
 __global__ void st_zero_kernel(int32_t* __restrict__ sizes, int G) {
     for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < G; x += gridDim.x * blockDim.x) sizes[x] = 0;
 }
@@ -68,6 +92,12 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
     __shared__ int lds_cnt[CNT_CAP];
     const int tid = threadIdx.x;
     const int s = blockIdx.x;
+    // the first pass of the walk below needs nothing of the schedule: its loads go out first and are in flight while
+    // the windows are worked out (the kernel is a chain of dependent memory round trips otherwise)
+    const int32_t* src = ids + (size_t)s * per_src;
+    int e_first[ST_ITEMS];
+#pragma unroll
+    for (int k = 0; k < ST_ITEMS; ++k) e_first[k] = tid * ST_ITEMS + k < per_src ? src[tid * ST_ITEMS + k] : -1;
     int K = *count_ptr;
     K = K < 0 ? 0 : (K > kmax ? kmax : K);
     const long long amount = traffic[(size_t)s * N + r];
@@ -103,18 +133,23 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
     __syncthreads();
     const bool win_in_lds = W <= WIN_CAP;
 
-    // ---- walk the assignments in arrival order
+    // ---- walk the assignments in arrival order, ST_ITEMS consecutive ones per thread and pass (one block scan per pass)
     int q_base = 0;
-    const int32_t* src = ids + (size_t)s * per_src;
-    for (int x0 = 0; x0 < per_src; x0 += ST_THREADS) {
-        int x = x0 + tid;
-        int e = x < per_src ? src[x] : -1;
-        bool mine = (unsigned)e < (unsigned)E && e / e_loc == r;
+    const int e_lo = r * e_loc, e_hi = min(e_lo + e_loc, E);           // the receiver's experts
+    for (int x0 = 0; x0 < per_src; x0 += ST_THREADS * ST_ITEMS) {
+        const int first = x0 + tid * ST_ITEMS;
+        int e[ST_ITEMS];
+#pragma unroll
+        for (int k = 0; k < ST_ITEMS; ++k) e[k] = x0 == 0 ? e_first[k] : (first + k < per_src ? src[first + k] : -1);
+        int cnt = 0;
+#pragma unroll
+        for (int k = 0; k < ST_ITEMS; ++k) cnt += (e[k] >= e_lo && e[k] < e_hi) ? 1 : 0;
         int excl, tot;
-        unsigned long long dummy_i, dummy_t;
-        block_scan(sm, mine, 0ULL, tid, excl, dummy_i, tot, dummy_t);
-        if (mine) {
-            const int q = q_base + excl;
+        block_scan_counts(sm, cnt, tid, excl, tot);
+        int q = q_base + excl;
+#pragma unroll
+        for (int k = 0; k < ST_ITEMS; ++k) {
+            if (!(e[k] >= e_lo && e[k] < e_hi)) continue;
             // smallest window whose cumulative amount exceeds q; W means "not shipped"
             int lo = 0, hi = W;
             while (lo < hi) {
@@ -122,13 +157,14 @@ void st_count_kernel(const int32_t* __restrict__ ids, int N, int per_src, int E,
                 int cum = win_in_lds ? lds_win[mid].y : my_ws[mid].y;
                 if (cum > q) hi = mid; else lo = mid + 1;
             }
-            const int el = e % e_loc;
+            const int el = e[k] - e_lo;
             if (cnt_in_lds) {
                 atomicAdd(&lds_cnt[lo * e_loc + el], 1);
             } else {
                 int slice = s == r ? 0 : (lo < W ? (win_in_lds ? lds_win[lo].x : my_ws[lo].x) : kmax + 1);
                 atomicAdd(&sizes[(size_t)slice * e_loc + el], 1);
             }
+            ++q;
         }
         q_base += tot;
     }
