@@ -302,6 +302,25 @@ def test_slice_table_rows(lib, name, which):
         assert only[2] is None and np.array_equal(only[1].cpu().numpy(), arr.cpu().numpy())
 
 
+@pytest.mark.parametrize("T,topk", [(9001, 1), (8192, 1), (2731, 3), (5, 1), (20000, 2)])
+def test_slice_table_walk_passes(lib, T, topk):
+    """Assignments per source below, at and above what one pass of the walk covers, with ragged ends."""
+    say("slice table walk passes T=%d topk=%d" % (T, topk))
+    N, E, r = 5, 20, 3
+    rng = np.random.default_rng(T + topk)
+    ids = rng.integers(-2, E + 2, size=(N, T, topk)).astype(np.int32)
+    traffic, _ = oracle.route_histogram(ids, E)
+    kmax = 3
+    rp, rd, _ = oracle.decompose_greedy(traffic, kmax, zero_diag=True)
+    k = len(rd)
+    perms = np.zeros((kmax, N), dtype=np.uint8); perms[:k] = rp
+    dur = np.zeros(kmax, dtype=np.int32); dur[:k] = rd
+    off = lib.moe_slice_table(dev(ids), E, r, dev(traffic), dev(perms), dev(dur), dev(np.array([k], dtype=np.int32)), kmax)
+    torch.cuda.synchronize()
+    ref, _ = oracle.slice_table(ids, E, r, traffic, rp, rd, kmax, want_rows=False)
+    assert np.array_equal(off.cpu().numpy(), ref)
+
+
 def test_slice_table_rows_shapes_and_errors(lib):
     say("slice table rows shapes")
     rng = np.random.default_rng(8)
