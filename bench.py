@@ -82,11 +82,11 @@ def summarize_counters(workload, fetch_csv, write_csv):
                "see": "profiles/ffn_%s_hbm_traffic.md" % workload}, open(base + ".json", "w"), indent=1)
     lines = ["# HBM-side byte counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels (gemm1 = phase 1: gate/up + SwiGLU)" % workload,
              "", "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box, one counter per run; then the summary, no GPU needed):", ""]
-    for c in ("FETCH_SIZE", "WRITE_SIZE"):
-        lines.append("    rocprofv3 --pmc %s --output-format csv -d gpurun_out/pmc_%s -o p -- python3 bench.py --workload %s --steps 10 "
-                     "--warmup 2 --no-extras --no-cpu-baseline --calibration-copy" % (c, c, workload))
-    lines += ["    python3 bench.py --workload %s --summarize-counters gpurun_out/pmc_FETCH_SIZE/p_counter_collection.csv "
-              "gpurun_out/pmc_WRITE_SIZE/p_counter_collection.csv" % workload, "",
+    rel_csv = [os.path.relpath(os.path.abspath(c), ROOT) for c in (fetch_csv, write_csv)]      # as given on the command line
+    for c, path in zip(("FETCH_SIZE", "WRITE_SIZE"), rel_csv):
+        lines.append("    rocprofv3 --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s --steps 10 "
+                     "--warmup 2 --no-extras --no-cpu-baseline --calibration-copy" % (c, os.path.dirname(path), workload))
+    lines += ["    python3 bench.py --workload %s --summarize-counters %s %s" % (workload, rel_csv[0], rel_csv[1]), "",
               "Calibration: the plain device-to-device copy of 256 MiB (`--calibration-copy`, the largest __amd_rocclr_copyBuffer dispatch) reads",
               "FETCH_SIZE = %.1f and WRITE_SIZE = %.1f for 262144 KiB each way -> scale factors %.4f (fetch) and %.4f (write)."
               % (f["copy"], w["copy"], cal_f, cal_w), "",
@@ -115,7 +115,7 @@ def main():
         summarize_counters(args.workload, *args.summarize_counters)
         return
     if args.gpus != 1:
-        print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU only (the library has no multi-GPU path); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
