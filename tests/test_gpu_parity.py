@@ -456,6 +456,33 @@ def test_ffn_fp8_weights_expanded_once(lib):
     assert np.abs(outs[0] - outs[1]).max() <= 0.02 * scale
 
 
+@pytest.mark.parametrize("mapped", [False, True])
+def test_ffn_same_bits_every_run(lib, mapped):
+    """Tiles are handed to workgroups dynamically, but the arithmetic of a tile is fixed: the output of a call
+    must not change by a bit from run to run (a race inside the kernels would show here)."""
+    say("ffn same bits every run", mapped)
+    E_loc, d, f, S, M = 4, 1024, 768, 6, 21000
+    W = workloads.ffn_weights(E_loc, d, f, seed=5, dtype="bf16")
+    x = dev_bf16(workloads.activations(M, d, seed=6))
+    offsets = dev(workloads.random_offsets(S * E_loc, M, seed=7))
+    w = upload_weights(W)
+    rng = np.random.default_rng(8)
+    row_map = dev(rng.permutation(M).astype(np.int32))
+    row_gate = dev(rng.random(M, dtype=np.float32))
+    first = None
+    for _ in range(6):
+        if mapped:
+            y = lib.moe_expert_ffn_sliced_mapped(x, offsets, S, E_loc, w["w_gate"], w["w_up"], w["w_down"], row_map, row_gate)
+        else:
+            y = lib.moe_expert_ffn_sliced(x, offsets, S, E_loc, **w)
+        torch.cuda.synchronize()
+        bits = y.view(torch.int16)
+        if first is None:
+            first = bits.clone()
+        else:
+            assert torch.equal(first, bits)
+
+
 def test_ffn_edge_cases(lib):
     say("ffn edge cases")
     E_loc, d, f = 2, 256, 128
