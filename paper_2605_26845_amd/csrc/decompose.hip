@@ -577,60 +577,75 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                     j0 = j1;
                 }
             }
-        } else
-        for (int r = 0; r < N; ++r) {
-            if (bcast<NPL>(sigma, r) >= 0) continue;
-            int minv[NPL], way[NPL];
-            bool used[NPL], intree[NPL];
+        } else {
+            // The same search with NPL columns per lane; the sets of scanned columns are NPL uniform masks.
+            const Mask<NPL> cols = below<NPL>(N);
+            Mask<NPL> todo;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) { minv[s] = INT_MAX; way[s] = -1; used[s] = false; intree[s] = false; }
-            int i0 = r, j0 = -1;
-            for (int step = 0; step < N; ++step) {
+            for (int s = 0; s < NPL; ++s) todo.w[s] = ballot64(sigma[s] < 0) & cols.w[s];
+            while (todo.any()) {
+                const int r = todo.first();
+                todo.reset(r);
+                int dist[NPL], way[NPL];
+                Mask<NPL> used;                                          // columns that do not exist count as scanned
 #pragma unroll
-                for (int s = 0; s < NPL; ++s)
-                    if (lane == (i0 & 63) && s == (i0 >> 6)) intree[s] = true;
-                const int ui0 = bcast<NPL>(u, i0);
-                const T* row = R + i0 * N;
-                int local = INT_MAX;
+                for (int s = 0; s < NPL; ++s) { dist[s] = INT_MAX; way[s] = -1; used.w[s] = ~cols.w[s]; }
+                int i0 = r, j0 = -1, D = 0;
+                for (int step = 0; step < N; ++step) {
+                    const int base = D + bcast<NPL>(u, i0);              // row i0 entered the tree at distance D
+                    const T* row = R + i0 * N;
+                    int key[NPL], local = INT_MAX;
 #pragma unroll
-                for (int s = 0; s < NPL; ++s) {
-                    int j = lane + 64 * s;
-                    if (j < N && !used[s]) {
-                        int slack = ui0 + v[s] - row[j];
-                        if (slack < minv[s]) { minv[s] = slack; way[s] = j0; }
-                        local = min(local, minv[s]);
+                    for (int s = 0; s < NPL; ++s) {
+                        const int j = lane + 64 * s;
+                        const bool open = !__builtin_amdgcn_inverse_ballot_w64(used.w[s]);
+                        const int entry = (int)row[j < N ? j : N - 1];
+                        const int cand = open ? base + v[s] - entry : INT_MAX;
+                        way[s] = cand < dist[s] ? j0 : way[s];
+                        dist[s] = min(dist[s], cand);
+                        key[s] = open ? dist[s] : INT_MAX;
+                        local = min(local, key[s]);
                     }
-                }
-                const int delta = wave_min(local);
-                int j1 = -1;
+                    D = wave_min(local);                                 // (finite: row r is unmatched, so a column is free)
+                    int j1 = -1;
 #pragma unroll
-                for (int s = NPL - 1; s >= 0; --s) {
-                    int j = lane + 64 * s;
-                    unsigned long long m = ballot64(j < N && !used[s] && minv[s] == delta);
-                    if (m) j1 = 64 * s + __builtin_ctzll(m);
+                    for (int s = NPL - 1; s >= 0; --s) {
+                        const unsigned long long m = ballot64(key[s] == D);
+                        if (m) j1 = 64 * s + __builtin_ctzll(m);
+                    }
+                    used.set(j1);
+                    j0 = j1;
+                    i0 = bcast<NPL>(p, j1);
+                    if (i0 < 0) break;
+                }
+                // duals: a scanned column j rises by D - dist_j, its row falls by the same amount, row r falls by D
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) used.w[s] &= cols.w[s];
+                int du[NPL];
+#pragma unroll
+                for (int s = 0; s < NPL; ++s) {
+                    const int sg = sigma[s];                             // the column of this lane's row, if it has one
+                    const int src = sg < 0 ? 0 : sg;
+                    int dcol = __shfl(dist[0], src & 63);
+                    if (NPL > 1) { const int d1 = __shfl(dist[NPL - 1], src & 63); dcol = (src >> 6) ? d1 : dcol; }
+                    const bool rin = sg >= 0 && used.test(src);
+                    du[s] = lane + 64 * s == r ? D : (rin ? D - dcol : 0);
                 }
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) {
-                    if (used[s]) v[s] += delta;
-                    else if (minv[s] != INT_MAX) minv[s] -= delta;
-                    if (intree[s]) u[s] -= delta;
+                    if (__builtin_amdgcn_inverse_ballot_w64(used.w[s])) v[s] += D - dist[s];
+                    u[s] -= du[s];
                 }
-#pragma unroll
-                for (int s = 0; s < NPL; ++s)
-                    if (lane == (j1 & 63) && s == (j1 >> 6)) used[s] = true;
-                j0 = j1;
-                i0 = bcast<NPL>(p, j1);
-                if (i0 < 0) break;
-            }
-            // flip the path back to row r
-            for (int guard = 0; guard <= N; ++guard) {
-                int j1 = bcast<NPL>(way, j0);
-                int i = r;
-                if (j1 >= 0) i = bcast<NPL>(p, j1);
-                set_at<NPL>(p, j0, i, lane);
-                set_at<NPL>(sigma, i, j0, lane);
-                if (j1 < 0) break;
-                j0 = j1;
+                // flip the path back to row r
+                for (int guard = 0; guard <= N; ++guard) {
+                    int j1 = bcast<NPL>(way, j0);
+                    int i = r;
+                    if (j1 >= 0) i = bcast<NPL>(p, j1);
+                    set_at<NPL>(p, j0, i, lane);
+                    set_at<NPL>(sigma, i, j0, lane);
+                    if (j1 < 0) break;
+                    j0 = j1;
+                }
             }
         }
         // ---- canonical optimum: lexicographically smallest perfect matching of the tight graph
