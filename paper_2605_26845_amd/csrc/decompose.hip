@@ -507,25 +507,31 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
 #pragma unroll 4
                 for (int r = 0; r < N; ++r) reduce_row(r, (int)Rcol[r * N]);
             }
-        } else
-        for (int r = 0; r < N; ++r) {
-            const int ur = bcast<NPL>(u, r);
-            int slack[NPL], local = INT_MAX;
+        } else {
+            Mask<NPL> free_cols = below<NPL>(N);                       // columns nobody has taken yet
+            for (int r = 0; r < N; ++r) {
+                const T* row = R + r * N;
+                int x[NPL], local = INT_MIN;
 #pragma unroll
-            for (int s = 0; s < NPL; ++s) {
-                int j = lane + 64 * s;
-                slack[s] = j < N ? ur + v[s] - R[r * N + j] : INT_MAX;
-                local = min(local, slack[s]);
-            }
-            const int m = wave_min(local);
-            set_at<NPL>(u, r, ur - m, lane);
-            int pick = -1;
+                for (int s = 0; s < NPL; ++s) {
+                    const int j = lane + 64 * s;
+                    x[s] = j < N ? (int)row[j] - v[s] : INT_MIN;        // lanes without a column never win or tie
+                    local = max(local, x[s]);
+                }
+                const int m = wave_max(local);
+                set_at<NPL>(u, r, m, lane);
+                int pick = -1;
 #pragma unroll
-            for (int s = NPL - 1; s >= 0; --s) {
-                unsigned long long f = ballot64(slack[s] == m && p[s] < 0 && lane + 64 * s < N);
-                if (f) pick = 64 * s + __builtin_ctzll(f);
+                for (int s = NPL - 1; s >= 0; --s) {
+                    const unsigned long long f = ballot64(x[s] == m) & free_cols.w[s];
+                    if (f) pick = 64 * s + __builtin_ctzll(f);
+                }
+                if (pick >= 0) {
+                    free_cols.reset(pick);
+                    set_at<NPL>(p, pick, r, lane);
+                    set_at<NPL>(sigma, r, pick, lane);
+                }
             }
-            if (pick >= 0) { set_at<NPL>(p, pick, r, lane); set_at<NPL>(sigma, r, pick, lane); }
         }
         // ---- maximum-weight perfect matching: one shortest augmenting path per row still unmatched
         if constexpr (NPL == 1) {
