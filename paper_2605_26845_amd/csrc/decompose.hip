@@ -662,10 +662,11 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
             for (int s = 0; s < NPL; ++s) vv[s] = v[s];
             if constexpr (NW == 1) {
                 tm[0].clear();
+                const unsigned long long colmask = below<NPL>(N).w[0];
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
                     if (i < N) {
-                        const unsigned long long row = ballot64(lane < N && __builtin_amdgcn_readlane(u[0], i) + vv[0] == Rc[i]);
+                        const unsigned long long row = ballot64(__builtin_amdgcn_readlane(u[0], i) + vv[0] == Rc[i]) & colmask;
                         if (lane == i) tm[0].w[0] = row;
                     }
             } else {
