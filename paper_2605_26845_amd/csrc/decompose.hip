@@ -491,13 +491,11 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                 const int x = incol ? entry - v[0] : INT_MIN;             // lanes without a column never win or tie
                 const int m = wave_max_rows<NW>(x);
                 const unsigned long long avail = ballot64(x == m) & ~taken;
-                if (lane == r) u[0] = m;
-                if (avail) {
-                    const int pick = __builtin_ctzll(avail);
-                    taken |= 1ULL << pick;
-                    if (lane == pick) p[0] = r;
-                    if (lane == r) sigma[0] = pick;
-                }
+                // branch-free, so that the reductions of consecutive rows overlap: no free tight column = column -1
+                const int pick = __builtin_ffsll((long long)avail) - 1;
+                taken |= avail & (0ULL - avail);
+                if (lane == pick) p[0] = r;
+                if (lane == r) { u[0] = m; sigma[0] = pick; }
             };
             if constexpr (NW == 1) {
 #pragma unroll
