@@ -74,9 +74,31 @@ __device__ __forceinline__ int plan_scan(int v, int tid, int* wave_tot, int& tot
     return base + incl - v;
 }
 
+// two prefixes behind one pair of barriers
+__device__ __forceinline__ void plan_scan2(int a, int b, int tid, int* wave_a, int* wave_b, int& excl_a, int& excl_b, int& total_a,
+                                           int& total_b) {
+    const int lane = tid & 63, wave = tid >> 6;
+    int ia = a, ib = b;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int oa = __shfl_up(ia, off), ob = __shfl_up(ib, off);
+        if (lane >= off) { ia += oa; ib += ob; }
+    }
+    __syncthreads();
+    if (lane == 63) { wave_a[wave] = ia; wave_b[wave] = ib; }
+    __syncthreads();
+    int base_a = 0, base_b = 0;
+    total_a = 0; total_b = 0;
+    for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+        if (w < wave) { base_a += wave_a[w]; base_b += wave_b[w]; }
+        total_a += wave_a[w]; total_b += wave_b[w];
+    }
+    excl_a = base_a + ia - a;
+    excl_b = base_b + ib - b;
+}
 __global__ __launch_bounds__(PLAN_THREADS)
 void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int M, int bm, int cap, int4* __restrict__ plan) {
-    __shared__ int wave_tot[PLAN_THREADS / 64];
+    __shared__ int wave_tot[PLAN_THREADS / 64], wave_tot2[PLAN_THREADS / 64];
     const int tid = threadIdx.x;
     auto bounds = [&](int g, int& lo, int& hi) {
         lo = hi = 0;
@@ -85,15 +107,18 @@ void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int 
             hi = min(max(offsets[g + 1], lo), M);
         }
     };
-    // ---- number of partial blocks (groups whose size is not a multiple of bm)
-    int partial = 0;
-    for (int g = tid; g < G; g += PLAN_THREADS) {
-        int lo, hi;
-        bounds(g, lo, hi);
-        partial += (hi - lo) % bm != 0;
+    // ---- number of partial blocks (groups whose size is not a multiple of bm); with at most one group per thread
+    //      the scan of the table pass below yields it
+    int n_partial = 0;
+    if (G > PLAN_THREADS) {
+        int partial = 0;
+        for (int g = tid; g < G; g += PLAN_THREADS) {
+            int lo, hi;
+            bounds(g, lo, hi);
+            partial += (hi - lo) % bm != 0;
+        }
+        plan_scan(partial, tid, wave_tot, n_partial);
     }
-    int n_partial;
-    plan_scan(partial, tid, wave_tot, n_partial);
     // ---- table: partial blocks in group order, then the full blocks in group order
     int run_partial = 0, run_full = n_partial;                        // (uniform: every thread adds the same totals)
     for (int g0 = 0; g0 < G; g0 += PLAN_THREADS) {
@@ -101,11 +126,13 @@ void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int 
         int lo, hi;
         bounds(g, lo, hi);
         const int rows = hi - lo, nfull = rows / bm, has_partial = rows % bm != 0;
-        int tot;
-        const int at_partial = run_partial + plan_scan(has_partial, tid, wave_tot, tot);
-        run_partial += tot;
-        int at_full = run_full + plan_scan(nfull, tid, wave_tot, tot);
-        run_full += tot;
+        int ex_partial, ex_full, tot_partial, tot_full;
+        plan_scan2(has_partial, nfull, tid, wave_tot, wave_tot2, ex_partial, ex_full, tot_partial, tot_full);
+        if (G <= PLAN_THREADS) run_full = tot_partial;               // the only pass: all partial blocks are known now
+        const int at_partial = run_partial + ex_partial;
+        run_partial += tot_partial;
+        int at_full = run_full + ex_full;
+        run_full += tot_full;
         for (int k = 0; k < nfull; ++k, ++at_full)
             if (at_full < cap) plan[PLAN_HDR + at_full] = make_int4(lo + k * bm, hi, g % e_loc, bm > 128 ? 0 : 1);
         if (has_partial && at_partial < cap) {
