@@ -254,6 +254,38 @@ def test_bvn_closed_forms():
     assert len(lam) == 5 and np.array_equal(R, res)
 
 
+def test_bvn_padding_is_the_north_west_corner_fill():
+    """Where the padding goes (Section 3.1 needs equal line sums; any non-negative matrix with the right marginals would
+    balance, the decomposition differs).  Worked by hand: deficits r_i = T* - row sum, c_j = T* - column sum; start at
+    the north-west corner, put min(r_i, c_j) at (i, j), move down when the row is satisfied, right when the column is."""
+    # row sums 4,2,1; column sums 5,1,1; T* = 5; r = (1,3,4), c = (0,4,4)
+    A = np.array([[4, 0, 0], [1, 1, 0], [0, 0, 1]], dtype=np.int32)
+    _, lam, _, tot, pad = oracle.decompose_bvn(A)
+    assert tot == 5 and pad.tolist() == [[0, 1, 0], [0, 3, 0], [0, 0, 4]] and lam.sum() == 5
+    # row and column deficits tie at every step: r = c = (0,3,2) -> the fill runs down the diagonal
+    A = np.array([[5, 1, 0], [0, 2, 1], [1, 0, 3]], dtype=np.int32)
+    _, _, _, tot, pad = oracle.decompose_bvn(A)
+    assert tot == 6 and pad.tolist() == [[0, 0, 0], [0, 3, 0], [0, 0, 2]]
+    # 4 x 4, zero diagonal: row sums 4,3,5,3, column sums 3,4,3,5, T* = 5, r = (1,2,0,2), c = (2,1,2,0);
+    # the padding lands on the diagonal too (an idle circuit)
+    A = np.array([[0, 3, 1, 0], [2, 0, 0, 1], [0, 1, 0, 4], [1, 0, 2, 0]], dtype=np.int32)
+    for zd in (False, True):
+        _, _, _, tot, pad = oracle.decompose_bvn(A, zero_diag=zd)
+        assert tot == 5 and pad.tolist() == [[1, 0, 0, 0], [1, 1, 0, 0], [0, 0, 0, 0], [0, 0, 2, 0]]
+    # the flag zeroes the diagonal before the deficits are taken: 9 on the diagonal would otherwise set T* = 12
+    B = A.copy()
+    B[2, 2] = 7
+    _, _, _, tot, pad = oracle.decompose_bvn(B, zero_diag=True)
+    assert tot == 5 and pad.tolist() == [[1, 0, 0, 0], [1, 1, 0, 0], [0, 0, 0, 0], [0, 0, 2, 0]]
+    _, _, _, tot, pad = oracle.decompose_bvn(B, zero_diag=False)
+    # row sums 4,3,12,3, column sums 3,4,10,5: T* = 12, r = (8,9,0,9), c = (9,8,2,7)
+    assert tot == 12 and pad.tolist() == [[8, 0, 0, 0], [1, 8, 0, 0], [0, 0, 0, 0], [0, 0, 2, 7]]
+    # and the first matching on a hand-made padded matrix: the lexicographically first permutation inside the support
+    A = np.array([[4, 0, 0], [1, 1, 0], [0, 0, 1]], dtype=np.int32)          # padded: [[4,1,0],[1,4,0],[0,0,5]]
+    perms, lam, res, _, _ = oracle.decompose_bvn(A)
+    assert perms.tolist() == [[0, 1, 2], [1, 0, 2]] and lam.tolist() == [4, 1] and not res.any()
+
+
 def test_batch_driver_and_hash():
     mats = workloads.random_matrices(6, 16, seed=4, density=0.6, high=20, zero_diag=True)
     for which in ("greedy", "bvn"):

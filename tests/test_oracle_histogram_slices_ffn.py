@@ -187,3 +187,41 @@ def test_ffn_properties():
     # SwiGLU sign structure: swapping gate and up changes the result (catches a transposed operand)
     Wsw = workloads.FFNWeights("bf16", W.w_up, W.w_gate, W.w_down)
     assert not np.allclose(oracle.expert_ffn_sliced(x, off_a, E_loc, Wsw), y)
+
+
+def test_ffn_mapped_hand_example():
+    """Dispatch gather / combine scatter (Section 2.1) on two groups whose source rows, target rows and router weights
+    are written out: schedule row m reads arrival row row_map[m], its result times row_gate[m] belongs at the same
+    arrival row.  The reference is torch float64 with explicit index_select / index_copy."""
+    E_loc, d, f = 2, 128, 256
+    W = workloads.ffn_weights(E_loc, d, f, seed=21)
+    x = workloads.activations(7, d, seed=22)                            # 7 arrival rows, row 3 is never scheduled
+    offsets = np.array([0, 2, 6], dtype=np.int32)                       # group 0 = expert 0: schedule rows 0,1; group 1 = expert 1: rows 2..5
+    row_map = np.array([5, 0, 6, 2, 1, 4], dtype=np.int32)
+    gate = np.array([0.5, 0.25, 1.0, 0.125, 2.0, 0.75], dtype=np.float32)
+    y, target = oracle.expert_ffn_sliced_mapped(x, offsets, E_loc, W, row_map, gate)
+    assert list(target) == [5, 0, 6, 2, 1, 4]
+    dec = lambda b: torch.from_numpy(np.ascontiguousarray(b).view(np.int16).copy()).view(torch.bfloat16).double()
+    xt = dec(x)
+    out = torch.full((7, d), float("nan"), dtype=torch.float64)
+    for e, (src, gates) in enumerate([([5, 0], [0.5, 0.25]), ([6, 2, 1, 4], [1.0, 0.125, 2.0, 0.75])]):
+        idx = torch.tensor(src)
+        xe = xt.index_select(0, idx)                                                        # gather
+        ye = (torch.nn.functional.silu(xe @ dec(W.w_gate[e]).T) * (xe @ dec(W.w_up[e]).T)) @ dec(W.w_down[e]).T
+        out.index_copy_(0, idx, ye * torch.tensor(gates, dtype=torch.float64)[:, None])     # weighted scatter
+    got = np.full((7, d), np.nan)
+    got[target] = y
+    assert np.isnan(got[3]).all() and torch.isnan(out[3]).all()
+    keep = [0, 1, 2, 4, 5, 6]
+    assert np.allclose(got[keep], out.numpy()[keep], rtol=1e-12, atol=1e-14)
+    assert np.abs(got[keep]).max() > 1e-3
+    # no gate = unit gate; identity map = the plain call; a row sample returns the same rows and targets
+    y1, _ = oracle.expert_ffn_sliced_mapped(x, offsets, E_loc, W, row_map)
+    assert np.allclose(y1 * gate.astype(np.float64)[:, None], y, rtol=1e-12, atol=1e-16)
+    yi, ti = oracle.expert_ffn_sliced_mapped(x, offsets, E_loc, W, np.arange(6, dtype=np.int32))
+    assert list(ti) == list(range(6)) and np.allclose(yi, oracle.expert_ffn_sliced(x, offsets, E_loc, W), rtol=1e-12, atol=1e-16)
+    ys, ts = oracle.expert_ffn_sliced_mapped(x, offsets, E_loc, W, row_map, gate, rows=np.array([1, 4]))
+    assert list(ts) == [0, 1] and np.allclose(ys, y[[1, 4]], rtol=1e-12, atol=1e-16)
+    # the gate belongs to the schedule row, not to the arrival row: permuting the gates changes the result
+    yw, _ = oracle.expert_ffn_sliced_mapped(x, offsets, E_loc, W, row_map, gate[row_map.argsort()])
+    assert not np.allclose(yw, y)
