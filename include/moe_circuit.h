@@ -164,9 +164,9 @@ moe_status moe_slice_table_rows(const int32_t* ids, int N, int T, int topk, int 
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
- * moe_expert_ffn_sliced -- Section 2.1 (compute: each expert processes its assigned tokens),
- * issued for all slices of a schedule at once so that no launch is paid per matching
- * (Section 2.2: fixed launch / synchronisation overheads dominate small batches).
+ * moe_expert_ffn_sliced -- Section 2.1 (the compute step between dispatch and combine), issued
+ * for all slices of a schedule at once so that no launch is paid per matching (Section 2.2: what
+ * a small batch costs is mostly fixed overhead).
  * For every group g = slice*E_loc + e and every row m in [offsets[g], offsets[g+1]):
  *     y[m] = ( silu(x[m] Wg_e^T) * (x[m] Wu_e^T) ) Wd_e^T ,  silu(z) = z / (1 + exp(-z))
  * with bf16 inputs, fp32 accumulation, the hidden activation rounded to bf16 once, y to bf16.
@@ -182,9 +182,10 @@ moe_status moe_slice_table_rows(const int32_t* ids, int N, int T, int topk, int 
  *                   bytes: when there are at least 2048 rows per local expert on average the weights
  *                   are then expanded to bf16 once per call (the same values the kernels would form
  *                   tile by tile) and the faster bf16 kernels run
- * Limits: d % 256 == 0, f % 128 == 0, S*E_loc <= 65536, M*max(d,f) < 2^31; x, y, the weights and
- * the workspace 16-byte aligned (MOE_ERR_INVALID_ARG otherwise).  The sigmoid inside silu uses the
- * hardware reciprocal (within 1 ulp of the quotient, before the rounding to bf16).
+ * Limits: d % 256 == 0, f % 128 == 0, S*E_loc <= 65536, M < 2^31, d and f <= 2^22, d*f < 2^31
+ * (MOE_ERR_UNSUPPORTED_SHAPE otherwise; M*d may exceed 2^31: rows are addressed with 64 bits); x, y,
+ * the weights and the workspace 16-byte aligned (MOE_ERR_INVALID_ARG otherwise).  The sigmoid inside
+ * silu uses the hardware reciprocal (within 1 ulp of the quotient, before the rounding to bf16).
  * ------------------------------------------------------------------------------------------- */
 size_t     moe_ffn_workspace_bytes(int M, int d, int f);
 size_t     moe_ffn_expanded_weights_bytes(int E_loc, int d, int f);
@@ -213,6 +214,20 @@ moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t* offsets, i
                                         const float* s_gate, const float* s_up, const float* s_down,
                                         const int32_t* row_map, const float* row_gate,
                                         void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_ffn_tile_override -- test and measurement hook, not meant for production callers.  The FFN
+ * calls choose the height of their row blocks (64, 128 or 256 rows) and the kernel family (one
+ * whose tile shape adapts to ragged group ends, or fixed-shape tiles) from the shape of the
+ * schedule; this call pins either choice for all following moe_expert_ffn_sliced(_mapped) calls of
+ * the process, so that every kernel can be driven on small inputs and timed on any input.
+ *   tile_rows    0 = chosen per call (the default), else 64, 128 or 256
+ *   fixed_shape  0 = chosen per call (the default), 1 = always the fixed-shape kernels
+ * Process-wide and not synchronised with FFN calls running on other threads.  Results of any
+ * choice agree within the rounding of the fp32 sums (the order of the additions differs).
+ * Returns MOE_ERR_INVALID_ARG for other values (nothing changes then).
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape);
 
 /* ---------------------------------------------------------------------------------------------
  * moe_makespan_model -- Section 5 (Setup: "Execution time"), host-side.  Analytic completion time

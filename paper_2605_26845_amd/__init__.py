@@ -29,7 +29,7 @@ EXPORTS = [
     "moe_route_histogram", "moe_decompose_greedy", "moe_decompose_bvn", "moe_slice_table_workspace_bytes",
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_ffn_expanded_weights_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
-    "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped",
+    "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped", "moe_ffn_tile_override",
 ]
 
 _lib = None
@@ -101,6 +101,8 @@ def load():
     L.moe_ffn_expanded_weights_bytes.restype = sz
     L.moe_expert_ffn_sliced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moe_expert_ffn_sliced.restype = ci
+    L.moe_ffn_tile_override.argtypes = [ci, ci]
+    L.moe_ffn_tile_override.restype = ci
     L.moe_kernel_timing_enable.argtypes = [ci]
     L.moe_kernel_timing_enable.restype = ci
     L.moe_kernel_timing_select.argtypes = [ctypes.c_char_p]
@@ -335,6 +337,12 @@ def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, 
                                         _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(y), _ptr(workspace),
                                         workspace.numel(), _stream()), "moe_expert_ffn_sliced")
     return y
+
+
+def moe_ffn_tile_override(tile_rows: int = 0, fixed_shape: bool = False):
+    """Test / measurement hook: pin the row-block height (64, 128, 256; 0 = automatic) and / or the fixed-shape kernels
+    for the following FFN calls of this process.  Call with no arguments to restore the defaults."""
+    _check(load().moe_ffn_tile_override(int(tile_rows), 1 if fixed_shape else 0), "moe_ffn_tile_override")
 
 
 def moe_kernel_timing_enable(on: bool):

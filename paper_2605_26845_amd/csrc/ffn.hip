@@ -13,7 +13,6 @@
 // 8 bytes at a time.  bf16 schedules with large groups run ffn_adaptive_kernel, the others (and
 // fp8 weights) the fixed-shape ffn_gemm_kernel.
 #include "common.hpp"
-#include <stdlib.h>
 #include <type_traits>
 #include <algorithm>
 
@@ -290,7 +289,7 @@ void ffn_gemm_kernel(FfnArgs a) {
     const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
     const unsigned int b_voff = (unsigned int)(row0 * K + kcg * 8) * ESZ;
     int m0 = 0, m_end = 0, nt = 0;
-    int a_off[CA];
+    long long a_off[CA];                               // element offset of this thread's chunk (64 bit: M * K may pass 2^31)
     const unsigned char* bbase[CB];
     const float* sbase[CB];
     auto setup = [&](int blk, int nt_) {
@@ -301,7 +300,7 @@ void ffn_gemm_kernel(FfnArgs a) {
 #pragma unroll
         for (int i = 0; i < CA; ++i) {
             const int m = m0 + min(row0 + RS * i, rows - 1);
-            a_off[i] = (PHASE == 1 ? mapped_row(a, m) : m) * K + kcg * 8;
+            a_off[i] = (long long)(PHASE == 1 ? mapped_row(a, m) : m) * K + kcg * 8;
         }
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
@@ -550,9 +549,13 @@ constexpr int STAGE_OFF = 131072;                             // slab buffers be
 constexpr int STAGE_WAVE = 4096;                              // staging per wavefront: 32 rows x 128 bytes
 constexpr int ADAPTIVE_LDS = STAGE_OFF + 8 * STAGE_WAVE;      // 160 KiB: all of a compute unit's LDS
 
-template <int PHASE>
+// GATHER (phase 1 with a row map): the rows of a tile lie anywhere in x, so every thread carries the 64-bit address of
+// its rows; otherwise the rows of a tile are consecutive and one buffer descriptor per tile (64-bit base at the
+// tile's first row) plus 32-bit offsets inside the tile address them, whatever the size of the operand.
+template <int PHASE, bool GATHER>
 __global__ __launch_bounds__(512, 1)
 void ffn_adaptive_kernel(FfnArgs a) {
+    static_assert(PHASE == 1 || !GATHER, "only phase 1 gathers its rows");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // next tile: (block, tile index, class, first row, end row, expert); block -1 = none.  It shares its bytes with
     // wavefront 0's output staging: written by that wavefront after its read-out, read by the others before the
@@ -617,7 +620,8 @@ void ffn_adaptive_kernel(FfnArgs a) {
     // ---- per-tile copy state: buffer resources and scalar offsets carry what is uniform, the per-thread byte offsets
     //      are fixed for a tile, so a copy costs no vector ALU work.  Rows past the end of the block re-read its last row.
     const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
-    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)Abase, 0, 0xFFFFFFFF, 0x00020000);
+    unsigned long long aB = 0;                         // address of the tile's first row of the A operand (plain rows)
+    const unsigned char* a_ptr[GATHER ? 4 : 1];        // address of this thread's chunk of each of its rows (gathered rows)
     // B rows come from w_gate / w_up (phase 1) or w_down (phase 2) of the tile's expert: base address of the first and
     // distance to the second.  (One variable per quantity, set once per tile: a choice between variables inside the
     // unrolled copy code would keep them in memory.)
@@ -635,10 +639,16 @@ void ffn_adaptive_kernel(FfnArgs a) {
         const int e = __builtin_amdgcn_readfirstlane(s_ticket[5]);
         const int rows = min(C::BMc, m_end - m0);
         const int row0 = C::ROWB == 128 ? row0_128 : row0_64, kcg = C::ROWB == 128 ? kcg_128 : kcg_64;
+        if constexpr (GATHER) {
 #pragma unroll
-        for (int i = 0; i < C::CA; ++i) {
-            const int m = m0 + min(row0 + C::RPC * i, rows - 1);
-            a_voff[i] = (unsigned int)((PHASE == 1 ? mapped_row(a, m) : m) * K + kcg * 8) * 2u;
+            for (int i = 0; i < C::CA; ++i) {
+                const int m = m0 + min(row0 + C::RPC * i, rows - 1);
+                a_ptr[i] = (const unsigned char*)Abase + ((unsigned long long)(unsigned int)a.row_map[m] * (unsigned int)K + kcg * 8) * 2ull;
+            }
+        } else {
+            aB = (unsigned long long)Abase + (unsigned long long)(unsigned int)m0 * (unsigned int)K * 2ull;
+#pragma unroll
+            for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)(min(row0 + C::RPC * i, rows - 1) * K + kcg * 8) * 2u;
         }
         if (PHASE == 1) {
             wB = (unsigned long long)((const __bf16*)a.wg + (size_t)e * a.f * K);
@@ -664,8 +674,14 @@ void ffn_adaptive_kernel(FfnArgs a) {
         unsigned char* base = smem + sbuf * C::SLAB + wave_bytes;
         const int koff = s * C::ROWB;                           // (plain locals: the builtin's operands must not be dependent expressions)
         if (n < C::CA) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
+            if constexpr (GATHER) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_ptr[n] + koff),
+                                                 (__attribute__((address_space(3))) void*)(base + n * 8192), 16, 0, 0);
+            } else {
+                const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)aB, 0, 0xFFFFFFFF, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
                                                          a_voff[n], koff, 0, 0);
+            }
         } else {
             const int j = n - C::CA;
             const unsigned long long up = (j / CPSTRIP) & 1;
@@ -810,7 +826,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
                 // a barrier has passed since the next tile's ticket was written
                 nblk = __builtin_amdgcn_readfirstlane(s_ticket[0]); nnt = __builtin_amdgcn_readfirstlane(s_ticket[1]);
                 ncls = __builtin_amdgcn_readfirstlane(s_ticket[2]);
-                chained = nblk >= 0 && ncls == 0 && !(PHASE == 1 && a.row_map);
+                chained = nblk >= 0 && ncls == 0 && !GATHER;
                 // not chained: the two slots re-fetch this tile's slab 0 into the free buffer 0, which nobody reads
                 slab(NS - 2, 0, F, T, F, std::integral_constant<int, 1>{});
                 slab(NS - 1, 1, F, F, T, std::integral_constant<int, 2>{});
@@ -945,6 +961,8 @@ void ffn_expand_fp8_kernel(const unsigned char* __restrict__ codes, const float*
 int plan_capacity(int M) { return M / 64 + MAX_GROUPS + 1; }
 size_t h_bytes(int M, int f) { return (((size_t)M * f * 2) + 255) & ~(size_t)255; }
 
+std::atomic<int> g_force_rows{0};          // moe_ffn_tile_override: 0 = rows per tile chosen per call, else 64 / 128 / 256
+std::atomic<int> g_force_fixed{0};         //                        1 = never the adaptive-shape kernels
 std::atomic<int> g_num_cus[64];            // compute units of device d (0 = not asked yet)
 int num_cus() {
     int dev = 0, n = 0;
@@ -985,10 +1003,10 @@ moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     return k.done();
 }
 
-template <int PHASE>
+template <int PHASE, bool GATHER>
 moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     static moe::DeviceOnce attr;
-    auto kern = ffn_adaptive_kernel<PHASE>;
+    auto kern = ffn_adaptive_kernel<PHASE, GATHER>;
     int dev;
     if (attr.needed(dev)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ADAPTIVE_LDS);
@@ -1003,9 +1021,10 @@ moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s)
 }
 
 moe_status launch_both_adaptive(const FfnArgs& a, long long max_blocks, hipStream_t s) {
-    moe_status st = launch_adaptive<1>(a, max_blocks * (a.f / 128), s);
+    moe_status st = a.row_map ? launch_adaptive<1, true>(a, max_blocks * (a.f / 128), s)
+                              : launch_adaptive<1, false>(a, max_blocks * (a.f / 128), s);
     if (st != MOE_OK) return st;
-    return launch_adaptive<2>(a, max_blocks * (a.d / 256), s);
+    return launch_adaptive<2, false>(a, max_blocks * (a.d / 256), s);
 }
 
 template <int ROWS, bool FP8>
@@ -1020,6 +1039,14 @@ moe_status launch_both(const FfnArgs& a, long long max_blocks, hipStream_t s) {
 extern "C" size_t moe_ffn_workspace_bytes(int M, int d, int f) {
     if (M < 0 || d < 1 || f < 1) return 0;
     return h_bytes(M, f) + (size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4);
+}
+
+extern "C" moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape) {
+    if (tile_rows != 0 && tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return MOE_ERR_INVALID_ARG;
+    if (fixed_shape != 0 && fixed_shape != 1) return MOE_ERR_INVALID_ARG;
+    g_force_rows.store(tile_rows, std::memory_order_relaxed);
+    g_force_fixed.store(fixed_shape, std::memory_order_relaxed);
+    return MOE_OK;
 }
 
 extern "C" size_t moe_ffn_expanded_weights_bytes(int E_loc, int d, int f) {
@@ -1040,7 +1067,8 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     if (d % 256 != 0 || f % 128 != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
     const long long G = (long long)S * E_loc;
     if (G > MAX_GROUPS) return MOE_ERR_UNSUPPORTED_SHAPE;
-    if ((long long)M * (d > f ? d : f) >= (1LL << 31)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    // (32-bit byte offsets inside one 256-row tile and inside one expert's matrices)
+    if (d > (1 << 22) || f > (1 << 22) || (long long)d * f >= (1LL << 31)) return MOE_ERR_UNSUPPORTED_SHAPE;
     if (M == 0 || G == 0) return MOE_OK;
     if (!x || !y) return MOE_ERR_INVALID_ARG;
     // every operand is moved in 16-byte pieces
@@ -1074,10 +1102,7 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     // rows per tile: large groups take 256-row tiles, fragmented schedules smaller ones
     const long long avg = M / G;
     int bm = avg >= 768 ? 256 : (avg >= 96 ? 128 : 64);
-    if (const char* ov = getenv("MOE_FFN_ROWS")) {
-        int v = atoi(ov);
-        if (v == 64 || v == 128 || v == 256) bm = v;
-    }
+    if (const int forced = g_force_rows.load(std::memory_order_relaxed)) bm = forced;
 
     FfnArgs a;
     a.x = (const __bf16*)x;
@@ -1097,9 +1122,8 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
         if (st != MOE_OK) return st;
     }
     const long long max_blocks = M / bm + G;
-    const char* fixed = getenv("MOE_FFN_FIXED_SHAPE");
     // (the adaptive kernel chains tiles over their last two slabs: at least four 64-wide slabs, f >= 256; d always is)
-    if (bm == 256 && !fp8 && f >= 256 && !(fixed && fixed[0] == '1')) return launch_both_adaptive(a, max_blocks, s);
+    if (bm == 256 && !fp8 && f >= 256 && !g_force_fixed.load(std::memory_order_relaxed)) return launch_both_adaptive(a, max_blocks, s);
     if (fp8) {
         if (bm == 256) return launch_both<256, true>(a, max_blocks, s);
         if (bm == 128) return launch_both<128, true>(a, max_blocks, s);

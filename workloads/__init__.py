@@ -236,11 +236,27 @@ def activations(M: int, d: int, seed: int) -> np.ndarray:
     return out
 
 
-def random_offsets(n_groups: int, M: int, seed: int, empty_frac: float = 0.15) -> np.ndarray:
+def activations_on_device(M: int, d: int, seed: int, device):
+    """x[M][d] ~ N(0,1) as a bf16 torch tensor drawn on `device` (for row counts whose host copy would take minutes to
+    draw and gigabytes to hold); a checker reads back the rows it needs.  Seeded, but a different stream than
+    activations()."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed + 104729)
+    out = torch.empty((M, d), dtype=torch.bfloat16, device=device)
+    step = max(1, (1 << 26) // d)
+    for r0 in range(0, M, step):
+        r1 = min(M, r0 + step)
+        out[r0:r1] = torch.randn((r1 - r0, d), dtype=torch.float32, device=device, generator=g).to(torch.bfloat16)
+    return out
+
+
+def random_offsets(n_groups: int, M: int, seed: int, empty_frac: float = 0.15, power: float = 2.0) -> np.ndarray:
     """Ragged group boundaries: int32[n_groups+1], non-decreasing, offsets[0]=0, last=M,
-    with a share of empty groups."""
+    with a share of empty groups.  Group sizes ~ u^power, u uniform: a larger power gives a few large groups
+    among many small ones."""
     rng = np.random.default_rng(seed + 15485863)
-    w = rng.random(n_groups) ** 2
+    w = rng.random(n_groups) ** power
     w = w * (rng.random(n_groups) >= empty_frac)
     if w.sum() == 0:
         w[0] = 1.0
