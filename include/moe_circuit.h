@@ -145,6 +145,22 @@ moe_status moe_slice_table(const int32_t* ids, int N, int T, int topk, int E, in
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_slice_table_static -- moe_slice_table for callers that cannot hand over a workspace they
+ * allocated: code under HIP graph capture, tight serving loops, harnesses that forbid device
+ * allocation.  The work area is a fixed array of MOE_SLICE_TABLE_STATIC_BYTES inside the library's
+ * device image (every GPU the library runs on holds one for the life of the process); the call
+ * allocates and frees nothing.  Same arguments, same kernels and same results as moe_slice_table.
+ * Returns MOE_ERR_WORKSPACE when moe_slice_table_workspace_bytes(N, kmax, E) exceeds
+ * MOE_SLICE_TABLE_STATIC_BYTES (nothing is enqueued then): use moe_slice_table for such schedules.
+ * All calls on one GPU share that GPU's work area: two calls that overlap in time on the same GPU
+ * (different streams, or different threads) race; calls on one stream are ordered and safe.
+ * ------------------------------------------------------------------------------------------- */
+#define MOE_SLICE_TABLE_STATIC_BYTES (4u << 20)
+moe_status moe_slice_table_static(const int32_t* ids, int N, int T, int topk, int E, int r,
+                                  const int32_t* traffic, const uint8_t* perms, const int32_t* durations,
+                                  const int32_t* count, int kmax, int32_t* offsets, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * moe_slice_table_rows -- moe_slice_table plus the row map that turns "dispatch" into a gather
  * (Section 2.1: dispatch sends each token to its experts, combine returns the results): rows
  * reach rank r source by source, each source in its (token, slot) order; the schedule wants them

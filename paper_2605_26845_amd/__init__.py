@@ -30,6 +30,7 @@ EXPORTS = [
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_ffn_expanded_weights_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped", "moe_ffn_tile_override",
+    "moe_slice_table_static",
 ]
 
 _lib = None
@@ -89,6 +90,8 @@ def load():
     L.moe_slice_table_workspace_bytes.restype = sz
     L.moe_slice_table.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, sz, vp]
     L.moe_slice_table.restype = ci
+    L.moe_slice_table_static.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp]
+    L.moe_slice_table_static.restype = ci
     L.moe_slice_table_rows_workspace_bytes.argtypes = [ci, ci, ci]
     L.moe_slice_table_rows_workspace_bytes.restype = sz
     L.moe_slice_table_rows.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp, sz, vp]
@@ -250,6 +253,15 @@ def moe_slice_table(ids, E: int, r: int, traffic, perms, durations, count, kmax:
         workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=ids.device)
     _check(load().moe_slice_table(_ptr(ids), N, T, topk, E, r, _ptr(traffic), _ptr(perms), _ptr(durations), _ptr(count),
                                   kmax, _ptr(offsets), _ptr(workspace), workspace.numel(), _stream()), "moe_slice_table")
+    return offsets
+
+
+def moe_slice_table_static(ids, E: int, r: int, traffic, perms, durations, count, kmax: int, offsets):
+    """moe_slice_table on the library's built-in work area; `offsets` int32 [(kmax+2)*E_loc+1] is the caller's.
+    Nothing is allocated here or in the library."""
+    N, T, topk = ids.shape
+    _check(load().moe_slice_table_static(_ptr(ids), N, T, topk, E, r, _ptr(traffic), _ptr(perms), _ptr(durations), _ptr(count),
+                                         kmax, _ptr(offsets), _stream()), "moe_slice_table_static")
     return offsets
 
 

@@ -13,6 +13,11 @@ constexpr int ST_ITEMS = 8;         // assignments one thread takes per pass of 
 constexpr int WIN_CAP = 2048;      // windows of one source kept in LDS (more spill to the workspace)
 constexpr int CNT_CAP = 8192;      // (window, expert) counters of one source kept in LDS
 
+// Work area of moe_slice_table_static: device memory owned by the library instead of a caller's workspace.  Every
+// GPU the library runs on holds its own copy at its own address (looked up once per device, see static_scratch()).
+constexpr size_t SCRATCH_BYTES = MOE_SLICE_TABLE_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+
 struct ScanSmem {
     int wave_cnt[ST_WAVES];
     unsigned long long wave_sum[ST_WAVES];
@@ -400,7 +405,41 @@ moe_status slice_table_impl(const int32_t* ids, int N, int T, int topk, int E, i
     return k.done();
 }
 
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle for the runtime,
+// not a device address: the address is asked for once per device, with that device current, and kept.
+std::atomic<void*> g_scratch_ptr[64];
+moe_status static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { moe::note_hip_error(e, "hipGetDevice"); return MOE_ERR_HIP; }
+    if (dev < 0 || dev >= 64) return MOE_ERR_UNSUPPORTED_SHAPE;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) { moe::note_hip_error(e, "hipGetSymbolAddress(scratch)"); return MOE_ERR_HIP; }
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return MOE_OK;
+}
+
 }  // namespace
+
+extern "C" moe_status moe_slice_table_static(const int32_t* ids, int N, int T, int topk, int E, int r, const int32_t* traffic,
+                                             const uint8_t* perms, const int32_t* durations, const int32_t* count, int kmax,
+                                             int32_t* offsets, void* hip_stream) {
+    if (N < 1 || kmax < 0 || E < 1) return MOE_ERR_INVALID_ARG;
+    if (E % N != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
+    const size_t need = moe_slice_table_workspace_bytes(N, kmax, E);
+    if (need == 0 || need > SCRATCH_BYTES) return MOE_ERR_WORKSPACE;      // the schedule is too long for the built-in work area
+    void* ws = nullptr;
+    moe_status st = static_scratch(&ws);
+    if (st != MOE_OK) return st;
+    // (nothing in the work area has to start at zero: the window lists are written before they are read, and the
+    //  group sizes are either written in full by every source or cleared by the zeroing kernel of the sparse path)
+    return slice_table_impl(ids, N, T, topk, E, r, traffic, perms, durations, count, kmax, offsets, false, nullptr, nullptr,
+                            ws, SCRATCH_BYTES, hip_stream);
+}
 
 extern "C" size_t moe_slice_table_workspace_bytes(int N, int kmax, int E) {
     if (N < 1 || kmax < 0 || E < 1 || E % N != 0) return 0;
