@@ -7,6 +7,10 @@ One step = one pass of the whole path over one batch of synthetic routing:
                       -> slice table of the receiving rank -> sliced expert SwiGLU FFN
 All inputs (router ids, weights, grouped activations) are resident in HBM before the timed
 region.  Prints ONE JSON line.  `value` = algorithmic FFN flops of the step / whole step time.
+
+The default workload is the largest bf16 configuration that fits one GPU (c3: one 4096 x 14336
+SwiGLU expert, hottest receiving rank).  The other configurations are reported beside it in
+`extras` (FFN only for c2 and c4, the batched 128 x 128 decomposition stress workload).
 """
 import argparse
 import json
@@ -20,14 +24,17 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
+SHADER_CLOCK_GHZ = 2.4              # published peak engine clock
+VALU_LANES = 256 * 4 * 16           # compute units x SIMDs x lanes: one 32-bit integer operation per lane and cycle
+LDS_BYTES_PER_CU = 160 * 1024
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["tiny", "c2", "c3"])
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["tiny", "c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -35,9 +42,16 @@ def parse():
     ap.add_argument("--summarize-counters", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: turn the counter_collection.csv files of the two rocprofv3 --pmc runs (FETCH_SIZE, "
                          "WRITE_SIZE; both with --calibration-copy) into profiles/ffn_<workload>_hbm_traffic.{md,json}")
+    ap.add_argument("--summarize-kernel-stats", metavar="STATS_CSV",
+                    help="no GPU work: turn the kernel_stats.csv of a rocprofv3 --kernel-trace --stats run of this script "
+                         "into profiles/ffn_<workload>_kernel_stats.md")
+    ap.add_argument("--summarize-mfma", metavar="COUNTER_CSV",
+                    help="no GPU work: turn the counter_collection.csv of the MFMA-utilisation --pmc run of this script "
+                         "into profiles/ffn_<workload>_mfma_utilisation.md")
     return ap.parse_args()
 
 
+# ------------------------------------------------------------------------------------------------ profile summaries (no GPU)
 def code_digest(path):
     """SHA-256 of a source file without its // comments and blank space: a stored counter figure stays valid across
     edits that cannot change the kernel."""
@@ -50,20 +64,39 @@ def code_digest(path):
     return hashlib.sha256("\n".join(lines).encode()).hexdigest()
 
 
+def kernel_key(name):
+    """Library kernel behind a profiler kernel name."""
+    if "ffn_adaptive_kernel<1" in name or "ffn_gemm_kernel<1," in name:
+        return "ffn_gemm1_kernel"
+    if "ffn_adaptive_kernel<2" in name or "ffn_gemm_kernel<2," in name:
+        return "ffn_gemm2_kernel"
+    if "copyBuffer" in name:
+        return "copy"
+    for k in ("bvn_kernel", "greedy_kernel", "st_count_kernel", "st_scan_kernel", "ffn_plan_kernel", "hist_kernel", "ffn_expand_fp8_kernel"):
+        if k in name:
+            return k
+    return None
+
+
+def workload_shape(workload):
+    import numpy as np
+    import workloads
+    cfg = workloads.CONFIGS[workload]
+    dest = workloads.config_routing(cfg) // cfg.E_loc
+    M = int(np.bincount(dest.ravel(), minlength=cfg.N).max())                  # rows of the hottest receiving rank
+    return cfg, M
+
+
 def summarize_counters(workload, fetch_csv, write_csv):
     """FETCH_SIZE / WRITE_SIZE (KiB per dispatch) of the two FFN kernels, scaled by what the same counter reads for the
     256 MiB calibration copy; stored with the SHA-256 of the kernel source it was measured on."""
     import collections
     import csv
-    import hashlib
 
     def averages(path):
         acc = collections.defaultdict(list)
         for row in csv.DictReader(open(path)):
-            k = row["Kernel_Name"]
-            key = ("ffn_gemm1_kernel" if "ffn_adaptive_kernel<1>" in k or "ffn_gemm_kernel<1," in k else
-                   "ffn_gemm2_kernel" if "ffn_adaptive_kernel<2>" in k or "ffn_gemm_kernel<2," in k else
-                   "copy" if "copyBuffer" in k else None)
+            key = kernel_key(row["Kernel_Name"])
             if key:
                 acc[key].append(float(row["Counter_Value"]))
         return {k: (max(v) if k == "copy" else sum(v) / len(v)) for k, v in acc.items()}     # the copy: its largest dispatch
@@ -79,6 +112,7 @@ def summarize_counters(workload, fetch_csv, write_csv):
     base = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic" % workload)
     json.dump({"kernel": "ffn_gemm1_kernel", "workload": workload, "source_sha256": {rel: sha},
                "traffic_bytes_per_launch": detail["ffn_gemm1_kernel"]["total_bytes"], "detail": detail,
+               "calibration_factor": {"FETCH_SIZE": cal_f, "WRITE_SIZE": cal_w},
                "see": "profiles/ffn_%s_hbm_traffic.md" % workload}, open(base + ".json", "w"), indent=1)
     lines = ["# HBM-side byte counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels (gemm1 = phase 1: gate/up + SwiGLU)" % workload,
              "", "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box, one counter per run; then the summary, no GPU needed):", ""]
@@ -94,25 +128,264 @@ def summarize_counters(workload, fetch_csv, write_csv):
     for k in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
         d = detail[k]
         lines.append("| %s | %.0f | %.0f | %.1f | %.1f | %.1f |" % (k, f[k], w[k], d["read_bytes"] / 1e6, d["write_bytes"] / 1e6, d["total_bytes"] / 1e6))
-    import numpy as np
-    import workloads
-    cfg = workloads.CONFIGS[workload]
-    dest = workloads.config_routing(cfg) // cfg.E_loc
-    M = int(np.bincount(dest.ravel(), minlength=cfg.N).max())                  # rows of the hottest receiving rank
+    cfg, M = workload_shape(workload)
     xb, wb_, hb = M * cfg.d * 2, 2 * cfg.E_loc * cfg.d * cfg.f * 2, M * cfg.f * 2
     lines += ["", "Algorithmic bytes of ffn_gemm1_kernel at this workload (M=%d, d=%d, f=%d, %d experts): x %.1f MB + gate/up weights %.1f MB read,"
               % (M, cfg.d, cfg.f, cfg.E_loc, xb / 1e6, wb_ / 1e6),
-              "h %.1f MB written = %.1f MB." % (hb / 1e6, (xb + wb_ + hb) / 1e6)]
-    lines += ["The fetch counter sits between the L2 and the fabric: it also counts reads served by the 256 MB memory-side cache.",
+              "h %.1f MB written = %.1f MB; ffn_gemm2_kernel: h %.1f MB + down weights %.1f MB read, y %.1f MB written = %.1f MB."
+              % (hb / 1e6, (xb + wb_ + hb) / 1e6, hb / 1e6, wb_ / 2e6, xb / 1e6, (hb + wb_ / 2 + xb) / 1e6),
+              "The fetch counter sits between the L2 and the fabric: it also counts reads served by the 256 MB memory-side cache.",
               "The stored figure (`.json`) carries the SHA-256 of ffn.hip (comments and blank space removed) it was measured on; bench.py reports it as `roofline.traffic` only while that matches.", ""]
     open(base + ".md", "w").write("\n".join(lines))
     print(base + ".md")
+
+
+def summarize_kernel_stats(workload, stats_csv):
+    import csv
+    cfg, M = workload_shape(workload)
+    rel = os.path.relpath(os.path.abspath(stats_csv), ROOT)
+    out_dir, prefix = os.path.dirname(rel), os.path.basename(rel).replace("_kernel_stats.csv", "")
+    lines = ["# rocprofv3 kernel-trace summary: bench.py, workload %s (N=%d, %d experts, top-%d, %d tokens/rank; %d experts d=%d f=%d; hottest rank: %d rows)"
+             % (workload, cfg.N, cfg.E, cfg.topk, cfg.T, cfg.E_loc, cfg.d, cfg.f, M), "",
+             "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box; then the summary, no GPU needed):", "",
+             "    rocprofv3 --kernel-trace --stats --output-format csv -d %s -o %s -- python3 bench.py --workload %s --steps 20 --no-extras --no-cpu-baseline"
+             % (out_dir, prefix, workload),
+             "    python3 bench.py --workload %s --summarize-kernel-stats %s" % (workload, rel), "",
+             "(library kernels only, times in microseconds)", "",
+             "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
+    avg = {}
+    for row in csv.DictReader(open(stats_csv)):
+        key = kernel_key(row["Name"])
+        if key is None or key == "copy":
+            continue
+        name = row["Name"].replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+        lines.append("| %s | %s | %.1f | %.1f | %.1f | %s |" % (name, row["Calls"], float(row["AverageNs"]) / 1e3, float(row["MinNs"]) / 1e3,
+                                                            float(row["MaxNs"]) / 1e3, row["Percentage"]))
+        avg[key] = float(row["AverageNs"]) / 1e3
+    f1, f2 = 4.0 * cfg.d * cfg.f * M, 2.0 * cfg.d * cfg.f * M
+    lines += ["", "bench.py reports the phase-1 kernel (gate/up projections + SwiGLU) as ffn_gemm1_kernel and the phase-2 kernel (down projection)",
+              "as ffn_gemm2_kernel; the phase-1 average here must agree with `roofline.avg_launch_us` of the same build's bench line (HIP events",
+              "inside the library; the profiler's own overhead and the box-to-box spread of about 5 % are the difference).",
+              "Phase 1: 4*d*f*M = %.4g flop per launch / %.1f us = %.0f TFLOP/s = %.3f of the 2.5 PFLOP/s bf16 MFMA peak."
+              % (f1, avg.get("ffn_gemm1_kernel", float("nan")), f1 / avg.get("ffn_gemm1_kernel", float("nan")) / 1e6,
+                 f1 / avg.get("ffn_gemm1_kernel", float("nan")) / 1e6 / MFMA_BF16_PEAK_TFLOPS),
+              "Phase 2: 2*d*f*M = %.4g flop per launch / %.1f us = %.0f TFLOP/s = %.3f of the peak."
+              % (f2, avg.get("ffn_gemm2_kernel", float("nan")), f2 / avg.get("ffn_gemm2_kernel", float("nan")) / 1e6,
+                 f2 / avg.get("ffn_gemm2_kernel", float("nan")) / 1e6 / MFMA_BF16_PEAK_TFLOPS), ""]
+    path = os.path.join(ROOT, "profiles", "ffn_%s_kernel_stats.md" % workload)
+    open(path, "w").write("\n".join(lines))
+    print(path)
+
+
+MFMA_COUNTERS = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES", "SQ_WAVE_CYCLES", "SQ_WAIT_ANY", "SQ_LDS_BANK_CONFLICT",
+                 "SQ_INSTS_VALU_MFMA_MOPS_BF16", "GRBM_GUI_ACTIVE"]
+
+
+def summarize_mfma(workload, counter_csv):
+    """MFMA utilisation of the FFN kernels from one rocprofv3 --pmc run (averages over the dispatches of each kernel)."""
+    import collections
+    import csv
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    dur = collections.defaultdict(dict)
+    for row in csv.DictReader(open(counter_csv)):
+        key = kernel_key(row["Kernel_Name"])
+        if key in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
+            acc[key][row["Counter_Name"]].append(float(row["Counter_Value"]))
+            dur[key][row["Dispatch_Id"]] = float(row["End_Timestamp"]) - float(row["Start_Timestamp"])
+    cfg, M = workload_shape(workload)
+    rel = os.path.relpath(os.path.abspath(counter_csv), ROOT)
+    lines = ["# MFMA utilisation counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels" % workload, "",
+             "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box; then the summary, no GPU needed):", "",
+             "    rocprofv3 --kernel-trace --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s --steps 10 --warmup 2 --no-extras --no-cpu-baseline"
+             % (" ".join(MFMA_COUNTERS), os.path.dirname(rel), workload),
+             "    python3 bench.py --workload %s --summarize-mfma %s" % (workload, rel), "",
+             "Averages per dispatch, as the profiler reports them: SQ_* counters are sums over the chip (SQ_VALU_MFMA_BUSY_CYCLES over its 1024 SIMDs,",
+             "SQ_BUSY_CU_CYCLES over its 256 compute units, SQ_WAVE_CYCLES / SQ_WAIT_ANY over all wavefronts), GRBM_GUI_ACTIVE is the sum of the busy",
+             "shader-clock cycles of the 8 accelerator dies (so cycles per launch = GRBM_GUI_ACTIVE / 8).", ""]
+    names = sorted({c for k in acc for c in acc[k]})
+    kernels = sorted(acc)
+    lines += ["| counter | " + " | ".join(kernels) + " |", "|---|" + "---|" * len(kernels)]
+    mean = {k: {c: sum(v) / len(v) for c, v in acc[k].items()} for k in kernels}
+    for c in names:
+        lines.append("| %s | " % c + " | ".join("%.4g" % mean[k].get(c, float("nan")) for k in kernels) + " |")
+    lines.append("| dispatches | " + " | ".join("%d" % len(dur[k]) for k in kernels) + " |")
+    lines.append("| average duration under the profiler, us | " + " | ".join("%.1f" % (sum(dur[k].values()) / len(dur[k]) / 1e3) for k in kernels) + " |")
+    lines.append("")
+    flops = {"ffn_gemm1_kernel": 4.0 * cfg.d * cfg.f * M, "ffn_gemm2_kernel": 2.0 * cfg.d * cfg.f * M}
+    peak_per_cycle = MFMA_BF16_PEAK_TFLOPS * 1e12 / (SHADER_CLOCK_GHZ * 1e9)
+    for k in kernels:
+        m = mean[k]
+        us = sum(dur[k].values()) / len(dur[k]) / 1e3
+        lines.append("%s:" % k)
+        if "GRBM_GUI_ACTIVE" in m:
+            cyc = m["GRBM_GUI_ACTIVE"] / 8.0
+            lines.append("- shader clock while it ran: %.3g cycles / %.1f us = %.2f GHz (%.1f GHz is the published peak clock the 2.5 PFLOP/s assume);" % (cyc, us, cyc / us / 1e3, SHADER_CLOCK_GHZ))
+            lines.append("- %.4g flop per launch / %.3g cycles = %.0f flop per cycle = %.3f of the %.0f flop per cycle of 256 compute units;" % (flops[k], cyc, flops[k] / cyc, flops[k] / cyc / peak_per_cycle, peak_per_cycle))
+            if "SQ_VALU_MFMA_BUSY_CYCLES" in m:
+                lines.append("- MFMA pipes busy %.1f %% of the launch's cycles (SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x cycles per launch));" % (100.0 * m["SQ_VALU_MFMA_BUSY_CYCLES"] / (1024.0 * cyc)))
+        if "SQ_VALU_MFMA_BUSY_CYCLES" in m and m.get("SQ_BUSY_CU_CYCLES", 0) > 0:
+            lines.append("- MFMA pipes busy %.1f %% of the cycles a compute unit had work (SQ_VALU_MFMA_BUSY_CYCLES / (4 x SQ_BUSY_CU_CYCLES));" % (100.0 * m["SQ_VALU_MFMA_BUSY_CYCLES"] / 4.0 / m["SQ_BUSY_CU_CYCLES"]))
+        if "SQ_WAIT_ANY" in m and m.get("SQ_WAVE_CYCLES", 0) > 0:
+            lines.append("- wavefronts waiting on a memory / LDS counter %.1f %% of their cycles (SQ_WAIT_ANY / SQ_WAVE_CYCLES);" % (100.0 * m["SQ_WAIT_ANY"] / m["SQ_WAVE_CYCLES"]))
+        if "SQ_LDS_BANK_CONFLICT" in m and m.get("SQ_BUSY_CU_CYCLES", 0) > 0:
+            lines.append("- LDS bank-conflict cycles: %.2f %% of the busy compute-unit cycles." % (100.0 * m["SQ_LDS_BANK_CONFLICT"] / m["SQ_BUSY_CU_CYCLES"]))
+        lines.append("")
+    path = os.path.join(ROOT, "profiles", "ffn_%s_mfma_utilisation.md" % workload)
+    open(path, "w").write("\n".join(lines))
+    print(path)
+
+
+def stored_traffic(workload):
+    """HBM-side bytes per launch of the dominant kernel from the committed counter summary (two rocprofv3 --pmc runs,
+    scaled by a plain copy of known size); None if that summary was taken on another workload or if the kernel's
+    source has changed since."""
+    path = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic.json" % workload)
+    try:
+        rec = json.load(open(path))
+        for rel, digest in rec["source_sha256"].items():
+            if code_digest(os.path.join(ROOT, rel)) != digest:
+                return None
+        return rec["traffic_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+# ------------------------------------------------------------------------------------------------ workloads on the device
+class Workload:
+    """Inputs of one configuration, resident in HBM: router ids, the hottest receiving rank, its expert weights and
+    activations, and every output / workspace buffer of the path."""
+
+    def __init__(self, moe, torch, np, workloads, cfg, dev, device_weights=False):
+        self.cfg = cfg
+        N, E, E_loc, kmax = cfg.N, cfg.E, cfg.E_loc, cfg.kmax
+        self.kb = (N - 1) * (N - 1) + 1                               # BvN is run uncapped
+        self.ids_h = workloads.config_routing(cfg)
+        self.ids = torch.from_numpy(self.ids_h).to(dev)
+        traffic, _ = moe.moe_route_histogram(self.ids, E)
+        torch.cuda.synchronize()
+        col = traffic.sum(0).cpu().numpy()
+        self.r = int(np.argmax(col))                                  # hottest receiving rank
+        self.M = M = int(col[self.r])
+        bf = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+        if device_weights:
+            self.W = None
+            self.w = workloads.ffn_weights_on_device(E_loc, cfg.d, cfg.f, cfg.seed, cfg.weight_dtype, dev)
+        else:
+            self.W = W = workloads.ffn_weights(E_loc, cfg.d, cfg.f, seed=cfg.seed, dtype=cfg.weight_dtype)
+            if W.dtype == "bf16":
+                self.w = dict(w_gate=bf(W.w_gate), w_up=bf(W.w_up), w_down=bf(W.w_down))
+            else:
+                up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+                self.w = dict(w_gate=up(W.w_gate), w_up=up(W.w_up), w_down=up(W.w_down), s_gate=up(W.s_gate), s_up=up(W.s_up), s_down=up(W.s_down))
+        self.x = workloads.activations_on_device(M, cfg.d, cfg.seed, dev)
+        self.S = S = kmax + 2
+        self.traffic = torch.empty((N, N), dtype=torch.int32, device=dev)
+        self.counts = torch.empty((N, E), dtype=torch.int32, device=dev)
+        self.g_out = dict(perms=torch.zeros((1, kmax, N), dtype=torch.uint8, device=dev),
+                          durations=torch.zeros((1, kmax), dtype=torch.int32, device=dev),
+                          counts=torch.zeros((1,), dtype=torch.int32, device=dev),
+                          residual=torch.empty((1, N, N), dtype=torch.int32, device=dev), hashes=None)
+        self.b_out = dict(perms=torch.zeros((1, self.kb, N), dtype=torch.uint8, device=dev),
+                          durations=torch.zeros((1, self.kb), dtype=torch.int32, device=dev),
+                          counts=torch.zeros((1,), dtype=torch.int32, device=dev),
+                          residual=torch.empty((1, N, N), dtype=torch.int32, device=dev), hashes=None,
+                          pad_total=torch.zeros((1,), dtype=torch.int32, device=dev))
+        self.offsets = torch.empty((S * E_loc + 1,), dtype=torch.int32, device=dev)
+        self.st_ws = torch.empty((moe.load().moe_slice_table_workspace_bytes(N, kmax, E),), dtype=torch.uint8, device=dev)
+        ws = moe.moe_ffn_workspace_bytes(M, cfg.d, cfg.f)
+        if cfg.weight_dtype == "fp8":
+            ws += moe.moe_ffn_expanded_weights_bytes(E_loc, cfg.d, cfg.f)
+        self.ffn_ws = torch.empty((ws,), dtype=torch.uint8, device=dev)
+        self.y = torch.empty_like(self.x)
+        self.moe, self.torch = moe, torch
+        self.main_stream = torch.cuda.current_stream()
+        self.side = torch.cuda.Stream()                               # default priority
+        self.ev_hist = torch.cuda.Event()
+        self.ev_bvn = torch.cuda.Event()
+
+    def describe(self):
+        c = self.cfg
+        return ("%s: N=%d ranks, %d experts (%d/rank), top-%d, %d tokens/rank, Zipf s=%.1f; greedy k<=%d vs BvN; receiving rank %d "
+                "(hottest) runs %d SwiGLU experts d=%d ffn=%d (%s weights) on %d rows in %d slices"
+                % (c.name, c.N, c.E, c.E_loc, c.topk, c.T, c.zipf_s, c.kmax, self.r, c.E_loc, c.d, c.f, c.weight_dtype, self.M, self.S))
+
+    def ffn(self):
+        self.moe.moe_expert_ffn_sliced(self.x, self.offsets, self.S, self.cfg.E_loc, y=self.y, workspace=self.ffn_ws, **self.w)
+
+    def step(self):
+        moe, torch, c = self.moe, self.torch, self.cfg
+        moe.moe_route_histogram(self.ids, c.E, traffic=self.traffic, expert_counts=self.counts)
+        self.ev_hist.record(self.main_stream)
+        with torch.cuda.stream(self.side):
+            self.side.wait_event(self.ev_hist)
+            moe.moe_decompose_bvn(self.traffic.unsqueeze(0), self.kb, zero_diag=True, out=self.b_out)
+            self.ev_bvn.record(self.side)
+        moe.moe_decompose_greedy(self.traffic.unsqueeze(0), c.kmax, zero_diag=True, out=self.g_out)
+        moe.moe_slice_table(self.ids, c.E, self.r, self.traffic, self.g_out["perms"][0], self.g_out["durations"][0],
+                            self.g_out["counts"], c.kmax, offsets=self.offsets, workspace=self.st_ws)
+        self.ffn()
+        self.main_stream.wait_event(self.ev_bvn)
+
+
+def ffn_entry(moe, torch, wl, reps):
+    """FFN figures of one workload from HIP events around every kernel: inside the whole step (the decompositions run
+    before and beside the FFN, as in the timed region of the main workload) and with the FFN call issued back to
+    back (the chip then never idles between two calls and settles at a lower clock under its power limit)."""
+    cfg, M = wl.cfg, wl.M
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        moe.moe_kernel_timing_select(None)
+        moe.moe_kernel_timing_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        moe.moe_kernel_timing_enable(False)
+        kt = moe.moe_kernel_timing_read()
+        return {k: v[0] * 1e3 / v[1] for k, v in kt.items()}, dt
+
+    step_us, step_s = timed(wl.step)
+    other = sum(v for k, v in step_us.items() if k in ("ffn_plan_kernel", "ffn_expand_fp8_kernel"))
+    e = ffn_figures(cfg, M, wl.S, step_us["ffn_gemm1_kernel"], step_us["ffn_gemm2_kernel"], other)
+    e["step_kernels_us"] = step_us
+    e["step_ms_with_an_event_pair_per_kernel"] = step_s * 1e3
+    b2b, _ = timed(wl.ffn)
+    e["back_to_back"] = {"phase1_us": b2b["ffn_gemm1_kernel"], "phase2_us": b2b["ffn_gemm2_kernel"],
+                         "phase1_frac_mfma_peak": 4.0 * cfg.d * cfg.f * M / b2b["ffn_gemm1_kernel"] / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+                         "phase2_frac_mfma_peak": 2.0 * cfg.d * cfg.f * M / b2b["ffn_gemm2_kernel"] / 1e6 / MFMA_BF16_PEAK_TFLOPS}
+    return e
+
+
+def ffn_figures(cfg, M, S, g1_us, g2_us, other_us):
+    f1, f2 = 4.0 * cfg.d * cfg.f * M, 2.0 * cfg.d * cfg.f * M
+    wbytes = (1 if cfg.weight_dtype == "fp8" else 2) * 3.0 * cfg.d * cfg.f * cfg.E_loc
+    abytes = 4.0 * cfg.d * M + 4.0 * cfg.f * M + wbytes                 # x in, y out, h written and read, weights once
+    intensity = (f1 + f2) / abytes
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    return {"rows": M, "slices": S, "experts": cfg.E_loc, "d": cfg.d, "f": cfg.f, "weights": cfg.weight_dtype,
+            "phase1_us": g1_us, "phase2_us": g2_us, "plan_and_other_kernels_us": other_us,
+            "phase1_tflops": f1 / g1_us / 1e6, "phase2_tflops": f2 / g2_us / 1e6,
+            "phase1_frac_mfma_peak": f1 / g1_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "phase2_frac_mfma_peak": f2 / g2_us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+            "ffn_tflops_kernels_only": (f1 + f2) / (g1_us + g2_us) / 1e6,
+            "frac_mfma_peak_kernels_only": (f1 + f2) / (g1_us + g2_us) / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+            "algorithmic_flop_per_byte": intensity, "bound": "mfma" if intensity > ridge else "hbm",
+            "note": "bf16 MFMA peak is the denominator for fp8 weights too: they are dequantised to bf16 on the way to the matrix cores"}
 
 
 def main():
     args = parse()
     if args.summarize_counters:
         summarize_counters(args.workload, *args.summarize_counters)
+        return
+    if args.summarize_kernel_stats:
+        summarize_kernel_stats(args.workload, args.summarize_kernel_stats)
+        return
+    if args.summarize_mfma:
+        summarize_mfma(args.workload, args.summarize_mfma)
         return
     if args.gpus != 1:
         print("bench.py measures one GPU only (the library has no multi-GPU path); run with --gpus 1", file=sys.stderr)
@@ -126,61 +399,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = workloads.CONFIGS[args.workload]
-    N, E, E_loc, kmax = cfg.N, cfg.E, cfg.E_loc, cfg.kmax
-    kb = (N - 1) * (N - 1) + 1                                   # BvN is run uncapped
-
-    # ---------------------------------------------------------------- inputs, resident in HBM
-    ids_h = workloads.config_routing(cfg)
-    ids = torch.from_numpy(ids_h).to(dev)
-    traffic, _ = moe.moe_route_histogram(ids, E)
-    torch.cuda.synchronize()
-    col = traffic.sum(0).cpu().numpy()
-    r = int(np.argmax(col))                                      # hottest receiving rank
-    M = int(col[r])
-    W = workloads.ffn_weights(E_loc, cfg.d, cfg.f, seed=cfg.seed, dtype=cfg.weight_dtype)
-    bf = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
-    wg, wu, wd = bf(W.w_gate), bf(W.w_up), bf(W.w_down)
-    x_h = workloads.activations(M, cfg.d, seed=cfg.seed)
-    x = bf(x_h)
-
-    # ---------------------------------------------------------------- preallocated outputs / workspaces
-    S = kmax + 2
-    traffic = torch.empty((N, N), dtype=torch.int32, device=dev)
-    counts = torch.empty((N, E), dtype=torch.int32, device=dev)
-    g_out = dict(perms=torch.zeros((1, kmax, N), dtype=torch.uint8, device=dev),
-                 durations=torch.zeros((1, kmax), dtype=torch.int32, device=dev),
-                 counts=torch.zeros((1,), dtype=torch.int32, device=dev),
-                 residual=torch.empty((1, N, N), dtype=torch.int32, device=dev), hashes=None)
-    b_out = dict(perms=torch.zeros((1, kb, N), dtype=torch.uint8, device=dev),
-                 durations=torch.zeros((1, kb), dtype=torch.int32, device=dev),
-                 counts=torch.zeros((1,), dtype=torch.int32, device=dev),
-                 residual=torch.empty((1, N, N), dtype=torch.int32, device=dev), hashes=None,
-                 pad_total=torch.zeros((1,), dtype=torch.int32, device=dev))
-    offsets = torch.empty((S * E_loc + 1,), dtype=torch.int32, device=dev)
-    st_ws = torch.empty((moe.load().moe_slice_table_workspace_bytes(N, kmax, E),), dtype=torch.uint8, device=dev)
-    ffn_ws = torch.empty((moe.moe_ffn_workspace_bytes(M, cfg.d, cfg.f),), dtype=torch.uint8, device=dev)
-    y = torch.empty_like(x)
-
-    main_stream = torch.cuda.current_stream()
-    side = torch.cuda.Stream()                                   # default priority
-    ev_hist = torch.cuda.Event()
-    ev_bvn = torch.cuda.Event()
-
-    def step():
-        moe.moe_route_histogram(ids, E, traffic=traffic, expert_counts=counts)
-        ev_hist.record(main_stream)
-        with torch.cuda.stream(side):
-            side.wait_event(ev_hist)
-            moe.moe_decompose_bvn(traffic.unsqueeze(0), kb, zero_diag=True, out=b_out)
-            ev_bvn.record(side)
-        moe.moe_decompose_greedy(traffic.unsqueeze(0), kmax, zero_diag=True, out=g_out)
-        moe.moe_slice_table(ids, E, r, traffic, g_out["perms"][0], g_out["durations"][0], g_out["counts"], kmax,
-                            offsets=offsets, workspace=st_ws)
-        moe.moe_expert_ffn_sliced(x, offsets, S, E_loc, wg, wu, wd, y=y, workspace=ffn_ws)
-        main_stream.wait_event(ev_bvn)
+    wl = Workload(moe, torch, np, workloads, cfg, dev)
+    M, N, kmax = wl.M, cfg.N, cfg.kmax
 
     for _ in range(args.warmup):
-        step()
+        wl.step()
     torch.cuda.synchronize()
     if args.calibration_copy:
         src = torch.ones((256 << 20,), dtype=torch.uint8, device=dev)
@@ -191,24 +414,24 @@ def main():
 
     # ---------------------------------------------------------------- timed region
     # HIP events bracket the dominant kernel only: an event pair costs about 7 us of stream time, and with one pair per
-    # kernel the step was measured 8 % slower than it is.  The other kernels are timed in a pass of their own below.
+    # kernel a step of small kernels is measured slower than it is.  The other kernels are timed in a pass of their own.
     moe.moe_kernel_timing_select("ffn_gemm1_kernel")
     moe.moe_kernel_timing_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        wl.step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     moe.moe_kernel_timing_enable(False)
     kt_dominant = moe.moe_kernel_timing_read()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    assert int(offsets[-1].item()) == M
+    assert int(wl.offsets[-1].item()) == M
     # ---------------------------------------------------------------- per-kernel breakdown (not part of the timed region)
     moe.moe_kernel_timing_select(None)
     moe.moe_kernel_timing_enable(True)
     for _ in range(max(5, args.steps // 2)):
-        step()
+        wl.step()
     torch.cuda.synchronize()
     moe.moe_kernel_timing_enable(False)
     kt = moe.moe_kernel_timing_read()
@@ -224,8 +447,8 @@ def main():
     roofline = {"kernel": "ffn_gemm1_kernel", "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": stored_traffic(args.workload),
                 "avg_launch_us": g1, "flop_per_launch": flops_g1}
-    n_match = int(g_out["counts"][0].item())
-    n_bvn = int(b_out["counts"][0].item())
+    n_match = int(wl.g_out["counts"][0].item())
+    n_bvn = int(wl.b_out["counts"][0].item())
     decomp_us = kernels["greedy_kernel"]["avg_us"]
     bvn_us = kernels["bvn_kernel"]["avg_us"]
     result = {
@@ -233,12 +456,11 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: N=%d ranks, %d experts (%d/rank), top-%d, %d tokens/rank, Zipf s=%.1f; greedy k<=%d vs BvN; "
-                               "receiving rank %d (hottest) runs %d SwiGLU experts d=%d ffn=%d on %d rows in %d slices"
-                               % (cfg.name, N, E, E_loc, cfg.topk, cfg.T, cfg.zipf_s, kmax, r, E_loc, cfg.d, cfg.f, M, S),
-                   "seed": cfg.seed},
+        "config": {"workload": wl.describe(), "seed": cfg.seed},
         "pct_mfma_peak_whole_step": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
         "ffn_tflops_kernels_only": flops_step / ((g1 + g2) * 1e-6) / 1e12,
+        "ffn_phase2": {"kernel": "ffn_gemm2_kernel", "avg_launch_us": g2, "achieved": 2.0 * cfg.d * cfg.f * M / g2 / 1e6,
+                       "frac": 2.0 * cfg.d * cfg.f * M / g2 / 1e6 / MFMA_BF16_PEAK_TFLOPS},
         "decompositions_per_s": {"greedy_%dx%d_k%d" % (N, N, kmax): 1e6 / decomp_us, "bvn_%dx%d_full" % (N, N): 1e6 / bvn_us,
                                  "greedy_matchings": n_match, "bvn_matchings": n_bvn},
         "kernels": kernels,
@@ -247,65 +469,162 @@ def main():
 
     # ---------------------------------------------------------------- extras outside the timed step
     if not args.no_extras:
-        result["extras"] = extras(moe, torch, np, workloads, dev)
-        result["extras"].update(ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ffn_ws))
-        result["extras"]["makespan_model_us"] = makespan_extras(moe, np, cfg, traffic, g_out, b_out,
-                                                                result["extras"]["expert_time_us_vs_rows"])
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r, x_h, W, M)
+        ex = result["extras"] = {}
+        other = sum(v["avg_us"] for k, v in kernels.items() if k in ("ffn_plan_kernel", "ffn_expand_fp8_kernel"))
+        ex["ffn_by_config"] = {cfg.name: ffn_figures(cfg, M, wl.S, g1, g2, other)}
+        ex["vendor_gemm_same_shape"] = vendor_gemm(torch, wl)
+        ex.update(ffn_granularity(moe, torch, np, wl))
+        ex["makespan_model_us"] = makespan_extras(moe, np, cfg, wl.traffic, wl.g_out, wl.b_out, ex["expert_time_us_vs_rows"])
+        x_sample, sample_rows = None, None
+        if not args.no_cpu_baseline:
+            sample_rows = np.unique(np.linspace(0, M - 1, num=min(M, cpu_sample_rows(cfg)), dtype=np.int64))
+            x_sample = wl.x[torch.from_numpy(sample_rows).to(dev)].view(torch.int16).cpu().numpy().view(np.uint16)
+        offsets_h = wl.offsets.cpu().numpy()
+        ids_h, r_main, W_main = wl.ids_h, wl.r, wl.W
+        del wl
+        torch.cuda.empty_cache()
+        for name in ("c2", "c3", "c4"):
+            if name == cfg.name:
+                continue
+            other_wl = Workload(moe, torch, np, workloads, workloads.CONFIGS[name], dev, device_weights=(name == "c4"))
+            ex["ffn_by_config"][name] = ffn_entry(moe, torch, other_wl, reps=10 if name == "c2" else 3)
+            ex["ffn_by_config"][name]["workload"] = other_wl.describe()
+            del other_wl
+            torch.cuda.empty_cache()
+        ex.update(decomposition_extras(moe, torch, np, workloads, dev, cpu=not args.no_cpu_baseline))
+        ex.update(histogram_and_sinkhorn_extras(moe, torch, np, workloads, dev))
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r_main, x_sample, sample_rows, offsets_h, W_main, M)
+            result["cpu_baseline"]["decomposition_stress"] = ex["decomposition_stress_128x128"].pop("cpu_oracle")
+    elif not args.no_cpu_baseline:
+        sample_rows = np.unique(np.linspace(0, M - 1, num=min(M, cpu_sample_rows(cfg)), dtype=np.int64))
+        x_sample = wl.x[torch.from_numpy(sample_rows).to(dev)].view(torch.int16).cpu().numpy().view(np.uint16)
+        result["cpu_baseline"] = cpu_baseline(cfg, wl.ids_h, wl.r, x_sample, sample_rows, wl.offsets.cpu().numpy(), wl.W, M)
     print(json.dumps(result))
 
 
-def stored_traffic(workload):
-    """HBM-side bytes per launch of the dominant kernel from the committed counter summary (two rocprofv3 --pmc runs,
-    scaled by a plain copy of known size); None if that summary was taken on another workload or if the kernel's
-    source has changed since."""
-    import hashlib
-    path = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic.json" % workload)
-    try:
-        rec = json.load(open(path))
-        for rel, digest in rec["source_sha256"].items():
-            if code_digest(os.path.join(ROOT, rel)) != digest:
-                return None
-        return rec["traffic_bytes_per_launch"]
-    except (OSError, KeyError, ValueError):
+def cpu_sample_rows(cfg):
+    """Rows of the FFN the CPU oracle evaluates: about 1.6e13 float64 flop (10 - 30 s on the host cores of a GPU machine,
+    whose BLAS sustains 0.5 - 1.5 TFLOP/s in float64)."""
+    return max(256, int(1.6e13 / (6.0 * cfg.d * cfg.f)))
+
+
+def vendor_gemm(torch, wl):
+    """torch.matmul (the vendor GEMM library) on the shape and data of phase 1: x [M][d] times the gate and up weights of
+    one expert [2f][d]^T.  Context for `roofline.frac`: what a dense, unsliced bf16 GEMM reaches on this data under the
+    same power and clock limits."""
+    if wl.cfg.weight_dtype != "bf16":
         return None
+    w = torch.cat([wl.w["w_gate"][0], wl.w["w_up"][0]], dim=0)            # [2f][d]
+    out = torch.empty((wl.M, w.shape[0]), dtype=torch.bfloat16, device=wl.x.device)
+    for _ in range(2):
+        torch.matmul(wl.x, w.t(), out=out)
+    torch.cuda.synchronize()
+    reps = 5
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        torch.matmul(wl.x, w.t(), out=out)
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / reps
+    flops = 2.0 * wl.M * w.shape[0] * wl.cfg.d
+    return {"shape": "[%d x %d] x [%d x %d]^T, bf16" % (wl.M, wl.cfg.d, w.shape[0], wl.cfg.d), "us": us, "tflops": flops / us / 1e6,
+            "frac_mfma_peak": flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS}
 
 
-def extras(moe, torch, np, workloads, dev):
-    """Batched decomposition (128 x 128 stress matrices) and batched-layer histogram rates."""
+def decomposition_extras(moe, torch, np, workloads, dev, cpu=True):
+    """The batched decomposition stress workload: 8192 independent 128 x 128 matrices, greedy k <= 32 (32-bit residual
+    on chip, and the default: 16 bits with a second launch for matrices that do not fit), full BvN on a stated subset,
+    with the two bounds that apply (integer ALU throughput; the dependent chain of one wavefront) and the CPU oracle."""
     out = {}
-    B = 2048
-    mats = torch.from_numpy(workloads.stress_matrices(B, 128)).to(dev)
-    bufs = dict(perms=torch.zeros((B, 32, 128), dtype=torch.uint8, device=dev),
-                durations=torch.zeros((B, 32), dtype=torch.int32, device=dev),
+    B, N, K = 8192, 128, 32
+    mats_h = workloads.stress_matrices(B, N)
+    mats = torch.from_numpy(mats_h).to(dev)
+    bufs = dict(perms=torch.zeros((B, K, N), dtype=torch.uint8, device=dev), durations=torch.zeros((B, K), dtype=torch.int32, device=dev),
                 counts=torch.zeros((B,), dtype=torch.int32, device=dev), residual=None, hashes=None)
-    moe.moe_decompose_greedy(mats, 32, zero_diag=True, out=bufs)
+    prof = torch.zeros((B, 4), dtype=torch.int64, device=dev)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    entry = {"matrices": B, "n": N, "kmax": K}
+    for label, bits in (("residual_32_bit", 32), ("default_16_bit_with_fallback", 0)):
+        dt = timed(lambda: moe.moe_decompose_greedy(mats, K, zero_diag=True, out=bufs, residual_bits=bits))
+        matchings = float(bufs["counts"].sum().item())
+        # counters of the same launch shape: shader clock the kernel ran at, steps of the augmenting-path searches
+        moe.moe_decompose_profile(prof)
+        moe.moe_decompose_greedy(mats, K, zero_diag=True, out=bufs, residual_bits=bits)
+        torch.cuda.synchronize()
+        moe.moe_decompose_profile(None)
+        p = prof.cpu().numpy().astype(np.float64)
+        clock_ghz = float((p[:, 0] / np.maximum(p[:, 1], 1.0)).mean() * 0.1)          # cycles per 10 ns tick
+        steps = float(p[:, 2].mean())
+        lds = N * N * (4 if bits == 32 else 2)
+        per_cu = min(LDS_BYTES_PER_CU // lds, 32)
+        # ALU bound: every step of a search relaxes one row of the residual, N columns at about 6 vector integer
+        # operations each (load, add, subtract, compare, two selects) plus the 6-stage minimum reduction; all lanes of
+        # the chip at the published clock
+        ops_per_matrix = steps * (N * 6.0 + 64 * 6.0)
+        alu_bound = VALU_LANES * SHADER_CLOCK_GHZ * 1e9 / ops_per_matrix
+        e = {"matrices_per_s": B / dt, "matchings_per_s": matchings / dt, "seconds": dt,
+             "lds_limited_wavefronts_per_cu": int(per_cu), "measured_shader_clock_ghz": clock_ghz,
+             "search_steps_per_matrix": steps, "searches_per_matrix": float(p[:, 3].mean()),
+             "cycles_per_matrix_in_batch": float(p[:, 0].mean()),
+             "alu_bound_matrices_per_s": alu_bound, "frac_alu_bound": B / dt / alu_bound,
+             "alu_bound_upper_work_k_n3_matrices_per_s": VALU_LANES * SHADER_CLOCK_GHZ * 1e9 / (K * float(N) ** 3 * 6.0)}
+        entry[label] = e
+    # dependency-chain bound: one wavefront alone on a compute unit is as fast as the chain of dependent steps allows;
+    # with w wavefronts resident per compute unit the chip cannot do better than 256 * w times that
+    few = 64
+    moe.moe_decompose_profile(prof)
+    moe.moe_decompose_greedy(mats[:few], K, zero_diag=True, out={k: (v[:few] if v is not None else None) for k, v in bufs.items()}, residual_bits=32)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    moe.moe_decompose_greedy(mats, 32, zero_diag=True, out=bufs)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    out["greedy_128x128_k32"] = {"matrices": B, "matrices_per_s": B / dt, "matchings_per_s": float(bufs["counts"].sum().item()) / dt}
-    # the same batch with the residual held in 16 bits (its entries are below 65536): twice the matrices in flight per CU
-    moe.moe_decompose_greedy(mats, 32, zero_diag=True, out=bufs, entries_u16=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    moe.moe_decompose_greedy(mats, 32, zero_diag=True, out=bufs, entries_u16=True)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    out["greedy_128x128_k32_u16"] = {"matrices": B, "matrices_per_s": B / dt, "matchings_per_s": float(bufs["counts"].sum().item()) / dt}
-    Bb = 256
+    moe.moe_decompose_profile(None)
+    p = prof[:few].cpu().numpy().astype(np.float64)
+    alone_s = float((p[:, 1] * 1e-8).mean())                                     # 100 MHz ticks
+    alone_clock = float((p[:, 0] / np.maximum(p[:, 1], 1.0)).mean() * 0.1)
+    entry["one_wavefront_alone"] = {"seconds_per_matrix": alone_s, "shader_clock_ghz": alone_clock,
+                                    "cycles_per_search_step": float((p[:, 0] / np.maximum(p[:, 2], 1.0)).mean())}
+    for label in ("residual_32_bit", "default_16_bit_with_fallback"):
+        e = entry[label]
+        e["chain_bound_matrices_per_s"] = 256 * e["lds_limited_wavefronts_per_cu"] / alone_s
+        e["frac_chain_bound"] = e["matrices_per_s"] / e["chain_bound_matrices_per_s"]
+    # full Birkhoff-von Neumann (uncapped: up to 16 130 matchings per matrix) on a subset, after a warm-up call
+    Bb = 512
+    kb = (N - 1) * (N - 1) + 1
     bb = dict(perms=None, durations=None, counts=torch.zeros((Bb,), dtype=torch.int32, device=dev), residual=None,
               hashes=None, pad_total=torch.zeros((Bb,), dtype=torch.int32, device=dev))
-    kb = 127 * 127 + 1
-    t0 = time.perf_counter()
-    moe.moe_decompose_bvn(mats[:Bb], kb, zero_diag=True, out=bb)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    out["bvn_128x128_full"] = {"matrices": Bb, "matrices_per_s": Bb / dt, "matchings_per_s": float(bb["counts"].sum().item()) / dt}
+    dt = timed(lambda: moe.moe_decompose_bvn(mats[:Bb], kb, zero_diag=True, out=bb))
+    entry["bvn_full"] = {"matrices": Bb, "of": B, "matrices_per_s": Bb / dt, "matchings_per_s": float(bb["counts"].sum().item()) / dt,
+                         "mean_matchings": float(bb["counts"].double().mean().item()), "seconds": dt,
+                         "lds_limited_wavefronts_per_cu": int(LDS_BYTES_PER_CU // (N * N * 4))}
+    if cpu:
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        ng, nb = 8 * threads, threads
+        t0 = time.perf_counter()
+        oracle.decompose_batch("greedy", mats_h[:ng], K, zero_diag=True, nthreads=threads, want_perms=False, want_residual=False)
+        tg = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.decompose_batch("bvn", mats_h[:nb], kb, zero_diag=True, nthreads=threads, want_perms=False, want_residual=False)
+        tb = time.perf_counter() - t0
+        entry["cpu_oracle"] = {"threads": threads, "greedy_k32": {"matrices": ng, "matrices_per_s": ng / tg, "seconds": tg},
+                               "bvn_full": {"matrices": nb, "matrices_per_s": nb / tb, "seconds": tb},
+                               "sample": "first %d (greedy) / %d (BvN) of the %d stress matrices, OpenMP over matrices" % (ng, nb, B)}
+    out["decomposition_stress_128x128"] = entry
+    return out
+
+
+def histogram_and_sinkhorn_extras(moe, torch, np, workloads, dev):
+    out = {}
     # the paper's own BvN pipeline (Sinkhorn-Knopp, then BvN in double precision) on dense 8 x 8 traffic (diagonal kept):
-    # its evaluation reports up to 50 matchings with many coefficients around 0.03
+    # Section 5 describes decompositions of about 50 matchings whose coefficients are a few hundredths
     B8 = 4096
     m8 = torch.from_numpy(workloads.random_matrices(B8, 8, seed=31, density=1.0, high=2000)).to(dev)
     moe.moe_decompose_sinkhorn_bvn(m8[:8], 50, sweeps=100, want_perms=False, want_scaled=False, want_residual=False)
@@ -335,17 +654,18 @@ def extras(moe, torch, np, workloads, dev):
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
     nbytes = ids.numel() * 4 + tr.numel() * 4 + cn.numel() * 4
-    out["histogram_64_layers"] = {"bytes": nbytes, "GB_per_s": nbytes / dt / 1e9, "frac_hbm_peak": nbytes / dt / 1e9 / HBM_PEAK_GBS}
+    out["histogram_64_layers"] = {"bytes": nbytes, "GB_per_s": nbytes / dt / 1e9, "frac_hbm_peak": nbytes / dt / 1e9 / HBM_PEAK_GBS, "bound": "hbm"}
     return out
 
 
-def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ffn_ws):
+def ffn_granularity(moe, torch, np, wl):
     """(i) the same schedule issued as one call per slice (what per-matching launches would cost) beside the single
     call; (ii) expert time against the number of rows of a single slice -- this GPU's version of the paper's Figure 1."""
     out = {}
+    cfg, x, y, offsets, S, E_loc, ffn_ws, w = wl.cfg, wl.x, wl.y, wl.offsets, wl.S, wl.cfg.E_loc, wl.ffn_ws, wl.w
     dev = x.device
     off_h = offsets.cpu().numpy().astype(np.int64)
-    reps = 20
+    reps = 20 if cfg.d * cfg.f < (1 << 24) else 5
 
     def timed(fn):
         fn()
@@ -356,7 +676,7 @@ def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ff
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps * 1e6
 
-    one_call = timed(lambda: moe.moe_expert_ffn_sliced(x, offsets, S, E_loc, wg, wu, wd, y=y, workspace=ffn_ws))
+    one_call = timed(lambda: moe.moe_expert_ffn_sliced(x, offsets, S, E_loc, y=y, workspace=ffn_ws, **w))
     per_slice = []
     for sl in range(S):
         lo, hi = int(off_h[sl * E_loc]), int(off_h[(sl + 1) * E_loc])
@@ -366,7 +686,7 @@ def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ff
 
     def run_slices():
         for xs, o, ys in per_slice:
-            moe.moe_expert_ffn_sliced(xs, o, 1, E_loc, wg, wu, wd, y=ys, workspace=ffn_ws)
+            moe.moe_expert_ffn_sliced(xs, o, 1, E_loc, y=ys, workspace=ffn_ws, **w)
 
     out["ffn_one_call_us"] = one_call
     # the same call with the dispatch gather / combine scatter fused in: rows in a random arrival order, router weights
@@ -375,8 +695,8 @@ def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ff
     M_used = int(off_h[-1])
     row_map = torch.randperm(M_used, device=dev, generator=g).to(torch.int32)
     gate = torch.rand((M_used,), device=dev, generator=g)
-    out["ffn_one_call_row_map_us"] = timed(lambda: moe.moe_expert_ffn_sliced_mapped(x, offsets, S, E_loc, wg, wu, wd, row_map,
-                                                                                    gate, y=y, workspace=ffn_ws))
+    out["ffn_one_call_row_map_us"] = timed(lambda: moe.moe_expert_ffn_sliced_mapped(x, offsets, S, E_loc, w["w_gate"], w["w_up"], w["w_down"],
+                                                                                    row_map, gate, y=y, workspace=ffn_ws))
     out["ffn_one_call_per_slice_us"] = timed(run_slices)
     out["ffn_slices"] = len(per_slice)
     curve = {}
@@ -384,7 +704,7 @@ def ffn_granularity(moe, torch, np, cfg, x, offsets, S, E_loc, wg, wu, wd, y, ff
         if rows > x.shape[0]:
             break
         o = torch.tensor([0, rows] + [rows] * (E_loc - 1), dtype=torch.int32, device=dev)      # all rows on local expert 0
-        curve[str(rows)] = timed(lambda: moe.moe_expert_ffn_sliced(x[:rows], o, 1, E_loc, wg, wu, wd, y=y[:rows], workspace=ffn_ws))
+        curve[str(rows)] = timed(lambda: moe.moe_expert_ffn_sliced(x[:rows], o, 1, E_loc, y=y[:rows], workspace=ffn_ws, **w))
     out["expert_time_us_vs_rows"] = curve
     return out
 
@@ -413,9 +733,20 @@ def makespan_extras(moe, np, cfg, traffic, g_out, b_out, curve):
     return out
 
 
-def cpu_baseline(cfg, ids_h, r, x_h, W, M):
-    """The CPU oracle, as it stands, on the same workload: integer stages in full, the FFN on a
-    bounded sample of rows.  Reported in the metric's unit."""
+class RowsView:
+    """Stands in for x[M][d] when only some rows were copied back to the host: indexing with a subset of `rows`."""
+    def __init__(self, data, rows, M):
+        self.data, self.rows, self.shape = data, rows, (M, data.shape[1])
+
+    def __getitem__(self, idx):
+        import numpy as np
+        pos = np.searchsorted(self.rows, idx)
+        return self.data[pos]
+
+
+def cpu_baseline(cfg, ids_h, r, x_sample, sample_rows, offsets_gpu, W, M):
+    """The CPU oracle, as it stands, on the same workload: integer stages in full, the FFN on a bounded sample of rows
+    (spread evenly over the schedule).  Reported in the metric's unit."""
     import numpy as np
     import oracle
     try:
@@ -435,14 +766,14 @@ def cpu_baseline(cfg, ids_h, r, x_h, W, M):
     t0 = time.perf_counter()
     offsets, _ = oracle.slice_table(ids_h, cfg.E, r, traffic, perms, dur, cfg.kmax, want_rows=False)
     t_slice = time.perf_counter() - t0
-    sample = M                                                   # the whole workload: a few seconds of CPU time
-    rows = np.arange(sample)
+    assert np.array_equal(offsets, offsets_gpu)
+    sample = len(sample_rows)
     t0 = time.perf_counter()
-    oracle.expert_ffn_sliced(x_h, offsets, cfg.E_loc, W, rows=rows)
+    oracle.expert_ffn_sliced(RowsView(x_sample, sample_rows, M), offsets, cfg.E_loc, W, rows=sample_rows)
     t_ffn = time.perf_counter() - t0
     tflops = 6.0 * cfg.d * cfg.f * sample / t_ffn / 1e12
     return {"value": tflops, "unit": "TFLOP/s", "cores": int(blas_threads), "kind": "oracle",
-            "sample": "FFN: %d of %d rows in float64 numpy (%.2f s, BLAS threads = cores); histogram %.1f ms, greedy %.2f ms, "
+            "sample": "FFN: %d of %d rows (evenly spaced) in float64 numpy (%.2f s, BLAS threads = cores); histogram %.1f ms, greedy %.2f ms, "
                       "BvN %.1f ms, slice table %.1f ms on the full workload, one thread each"
                       % (sample, M, t_ffn, t_hist * 1e3, t_greedy * 1e3, t_bvn * 1e3, t_slice * 1e3),
             "decompositions_per_s": {"greedy": 1.0 / t_greedy, "bvn": 1.0 / t_bvn}}

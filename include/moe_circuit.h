@@ -38,9 +38,12 @@ typedef int moe_status;
 
 /* flags of the decomposition calls */
 #define MOE_DECOMP_ZERO_DIAGONAL 1  /* treat the diagonal (tokens whose expert is local) as zero */
-#define MOE_DECOMP_ENTRIES_U16   2  /* moe_decompose_greedy only: the caller vouches that every entry is < 65536; the
-                                       residual is then kept in 16 bits (half the on-chip memory per matrix, twice
-                                       the matrices in flight).  A matrix with a larger entry gets counts[b] = -1. */
+/* moe_decompose_greedy keeps the residual of a matrix on chip, in 16 bits when that lets more matrices share a
+ * compute unit (N > 64 in batches that fill the chip more than twice over); a matrix with an entry >= 65536 is
+ * then decomposed again with a 32-bit residual by a second launch.  Results do not depend on the choice.  The two
+ * flags below pin it (tests, measurements); giving both is an error. */
+#define MOE_DECOMP_RESIDUAL_I32  2  /* 32-bit residual for every matrix                                        */
+#define MOE_DECOMP_RESIDUAL_U16  4  /* 16-bit first, whatever N and the batch size                             */
 
 /* weight formats of moe_expert_ffn_sliced */
 #define MOE_W_BF16            0   /* bfloat16                                                     */
@@ -97,6 +100,20 @@ moe_status moe_decompose_bvn(const int32_t* mats, int B, int N, int kmax, int fl
                              uint8_t* perms, int32_t* durations, int32_t* counts,
                              int32_t* residual, int32_t* pad_total, uint64_t* hashes,
                              void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * moe_decompose_profile -- measurement hook, not meant for production callers.  While a buffer is
+ * set, moe_decompose_greedy and moe_decompose_bvn record, for every matrix b < capacity, four
+ * 64-bit counters at counters[4 * b]: [0] shader clock cycles and [1] ticks of the constant
+ * 100 MHz real-time counter between the wavefront's first and last instruction (their ratio is the
+ * shader clock the kernel ran at), [2] steps of the augmenting-path searches (one step scans one
+ * row of the residual and settles one column) and [3] number of such searches (greedy only; zero
+ * for BvN).  The decompositions themselves are unchanged.
+ *   counters  device uint64 [4 * capacity], or NULL with capacity 0 to switch recording off
+ * Process-wide; the buffer must stay valid until the calls that were enqueued while it was set
+ * have finished.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_decompose_profile(uint64_t* counters, int capacity);
 
 /* ---------------------------------------------------------------------------------------------
  * moe_decompose_sinkhorn_bvn -- Section 3.1 as the paper describes it: Sinkhorn-Knopp scaling

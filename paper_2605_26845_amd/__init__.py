@@ -17,7 +17,8 @@ _LIB_PATH = os.path.join(_HERE, "libmoecircuit.so")
 _INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 
 MOE_DECOMP_ZERO_DIAGONAL = 1
-MOE_DECOMP_ENTRIES_U16 = 2
+MOE_DECOMP_RESIDUAL_I32 = 2
+MOE_DECOMP_RESIDUAL_U16 = 4
 MOE_W_BF16 = 0
 MOE_W_FP8_E4M3_B128 = 1
 MOE_MAX_RANKS = 128
@@ -30,7 +31,7 @@ EXPORTS = [
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_ffn_expanded_weights_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped", "moe_ffn_tile_override",
-    "moe_slice_table_static",
+    "moe_slice_table_static", "moe_decompose_profile",
 ]
 
 _lib = None
@@ -82,6 +83,8 @@ def load():
     L.moe_route_histogram.restype = ci
     L.moe_decompose_greedy.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     L.moe_decompose_greedy.restype = ci
+    L.moe_decompose_profile.argtypes = [vp, ci]
+    L.moe_decompose_profile.restype = ci
     L.moe_decompose_bvn.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     L.moe_decompose_bvn.restype = ci
     L.moe_decompose_sinkhorn_bvn.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, vp, vp, vp]
@@ -186,16 +189,28 @@ def _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out):
     return out
 
 
+def moe_decompose_profile(counters=None):
+    """Measurement hook: counters = device int64 tensor [capacity][4] that the following greedy / BvN calls fill per
+    matrix with (shader cycles, 100 MHz ticks, search steps, searches); None switches recording off."""
+    import torch
+    if counters is None:
+        _check(load().moe_decompose_profile(None, 0), "moe_decompose_profile")
+        return
+    _dev_check(counters, torch.int64, "counters")
+    _check(load().moe_decompose_profile(_ptr(counters), counters.numel() // 4), "moe_decompose_profile")
+
+
 def moe_decompose_greedy(mats, kmax: int, zero_diag: bool = False, want_perms=True, want_residual=True,
-                         want_hashes=False, out=None, entries_u16: bool = False):
+                         want_hashes=False, out=None, residual_bits: int = 0):
     """mats int32 [B][N][N] -> dict(perms, durations, counts, residual, hashes) of device tensors.
-    entries_u16: the caller vouches for entries < 65536 (16-bit residual on chip; counts[b] = -1 where that is false)."""
+    residual_bits: 0 = the library decides how the residual is held on chip, 32 / 16 pin it (same results)."""
     import torch
     _dev_check(mats, torch.int32, "mats")
     B, N, _ = mats.shape
     o = _decomp_buffers(mats, kmax, want_perms, want_residual, want_hashes, out)
     _check(load().moe_decompose_greedy(_ptr(mats), B, N, kmax,
-                                       (MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0) | (MOE_DECOMP_ENTRIES_U16 if entries_u16 else 0),
+                                       (MOE_DECOMP_ZERO_DIAGONAL if zero_diag else 0)
+                                       | {0: 0, 32: MOE_DECOMP_RESIDUAL_I32, 16: MOE_DECOMP_RESIDUAL_U16}[residual_bits],
                                        _ptr(o["perms"]), _ptr(o["durations"]), _ptr(o["counts"]), _ptr(o["residual"]),
                                        _ptr(o["hashes"]), _stream()), "moe_decompose_greedy")
     return o

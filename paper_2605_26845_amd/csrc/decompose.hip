@@ -20,6 +20,8 @@ namespace {
 
 constexpr unsigned long long FNV_OFFSET = 14695981039346656037ULL;
 constexpr unsigned long long FNV_PRIME = 1099511628211ULL;
+constexpr int REDO_MARKED = 0x100;     // internal flag of greedy_kernel: decompose only the matrices marked NOT_DONE
+constexpr int NOT_DONE = -1;           // counts[b] of a matrix the 16-bit pass could not hold
 
 // ------------------------------------------------------------------------------ wave primitives
 __device__ __forceinline__ int rdlane(int v, int l) {
@@ -435,13 +437,20 @@ template <int NPL, typename T, int NW>            // NW: 16-lane rows that hold 
 __global__ __launch_bounds__(MOE_WAVE)
 void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
                    int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
-                   unsigned long long* __restrict__ hashes) {
+                   unsigned long long* __restrict__ hashes, unsigned long long* __restrict__ prof, int prof_cap) {
     extern __shared__ __attribute__((aligned(16))) unsigned char greedy_lds[];
     T* R = reinterpret_cast<T*>(greedy_lds);           // T = uint16_t halves the footprint: twice the wavefronts per CU
     const int lane = threadIdx.x;
     const int b = blockIdx.x;
+    // second pass of a batch whose first pass kept the residual in 16 bits: only the matrices that pass marked
+    // (an entry did not fit) are decomposed, with the 32-bit residual
+    if ((flags & REDO_MARKED) && __builtin_amdgcn_readfirstlane(counts[b]) != NOT_DONE) return;
+    const bool profiled = prof != nullptr && b < prof_cap;
+    unsigned long long t_cycles = 0, t_real = 0;
+    int n_steps = 0, n_searches = 0;
+    if (profiled) { t_cycles = __builtin_readcyclecounter(); t_real = wall_clock64(); }
     if (!load_matrix(mats + (size_t)b * N * N, R, N, flags & MOE_DECOMP_ZERO_DIAGONAL, lane)) {
-        if (lane == 0) { counts[b] = -1; if (hashes) hashes[b] = 0; }      // an entry does not fit 16 bits
+        if (lane == 0) counts[b] = NOT_DONE;            // an entry does not fit 16 bits: left to the second pass
         return;
     }
 
@@ -560,8 +569,10 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                     used |= 1ULL << j1;
                     j0 = j1;
                     i0 = rdlane(p[0], j1);
+                    ++n_steps;
                     if (i0 < 0) break;
                 }
+                ++n_searches;
                 used &= ~beyond;
                 // duals: a scanned column j rises by D - dist_j, its row falls by the same amount, row r falls by D
                 // (tree edges stay tight, everything stays feasible, the new path is tight)
@@ -620,8 +631,10 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
                     used.set(j1);
                     j0 = j1;
                     i0 = bcast<NPL>(p, j1);
+                    ++n_steps;
                     if (i0 < 0) break;
                 }
+                ++n_searches;
                 // duals: a scanned column j rises by D - dist_j, its row falls by the same amount, row r falls by D
 #pragma unroll
                 for (int s = 0; s < NPL; ++s) used.w[s] &= cols.w[s];
@@ -693,6 +706,12 @@ void greedy_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags,
         if (hashes) hashes[b] = fnv.h;
     }
     if (residual) store_matrix(R, residual + (size_t)b * N * N, N, lane);
+    if (profiled && lane == 0) {
+        prof[4 * (size_t)b + 0] = __builtin_readcyclecounter() - t_cycles;
+        prof[4 * (size_t)b + 1] = wall_clock64() - t_real;
+        prof[4 * (size_t)b + 2] = (unsigned long long)n_steps;
+        prof[4 * (size_t)b + 3] = (unsigned long long)n_searches;
+    }
 }
 
 // ------------------------------------------------------------------------------ BvN kernel
@@ -701,10 +720,14 @@ template <int NPL, bool BOUND>             // BOUND (N > 32): the lexicographic 
 __global__ __launch_bounds__(MOE_WAVE)
 void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, uint8_t* __restrict__ perms,
                 int32_t* __restrict__ durations, int32_t* __restrict__ counts, int32_t* __restrict__ residual,
-                int32_t* __restrict__ pad_total, unsigned long long* __restrict__ hashes) {
+                int32_t* __restrict__ pad_total, unsigned long long* __restrict__ hashes,
+                unsigned long long* __restrict__ prof, int prof_cap) {
     extern __shared__ int32_t R[];
     const int lane = threadIdx.x;
     const int b = blockIdx.x;
+    const bool profiled = prof != nullptr && b < prof_cap;
+    unsigned long long t_cycles = 0, t_real = 0;
+    if (profiled) { t_cycles = __builtin_readcyclecounter(); t_real = wall_clock64(); }
     load_matrix(mats + (size_t)b * N * N, R, N, flags & MOE_DECOMP_ZERO_DIAGONAL, lane);
 
     // ---- integer padding to equal line sums (north-west-corner fill of the deficits)
@@ -884,6 +907,12 @@ void bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int flags, ui
         if (hashes) hashes[b] = fnv.h;
     }
     if (residual) store_matrix(R, residual + (size_t)b * N * N, N, lane);
+    if (profiled && lane == 0) {
+        prof[4 * (size_t)b + 0] = __builtin_readcyclecounter() - t_cycles;
+        prof[4 * (size_t)b + 1] = wall_clock64() - t_real;
+        prof[4 * (size_t)b + 2] = 0;
+        prof[4 * (size_t)b + 3] = 0;
+    }
 }
 
 // ------------------------------------------------------------------------------ Sinkhorn-Knopp + floating-point BvN kernel
@@ -1095,6 +1124,21 @@ void sinkhorn_bvn_kernel(const int32_t* __restrict__ mats, int N, int kmax, int 
     }
 }
 
+std::atomic<unsigned long long*> g_prof{nullptr};     // moe_decompose_profile: per-matrix counters of the following calls
+std::atomic<int> g_prof_cap{0};
+
+std::atomic<int> g_cus[64];
+int compute_units() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    n = g_cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        g_cus[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 moe_status check_args(const int32_t* mats, int B, int N, int kmax, int32_t* counts) {
     if (B < 0 || N < 1 || kmax < 0 || !counts) return MOE_ERR_INVALID_ARG;
     if (B > 0 && !mats) return MOE_ERR_INVALID_ARG;
@@ -1104,22 +1148,51 @@ moe_status check_args(const int32_t* mats, int B, int N, int kmax, int32_t* coun
 
 }  // namespace
 
+extern "C" moe_status moe_decompose_profile(uint64_t* counters, int capacity) {
+    if (capacity < 0 || (capacity > 0 && !counters)) return MOE_ERR_INVALID_ARG;
+    g_prof.store(capacity > 0 ? (unsigned long long*)counters : nullptr, std::memory_order_relaxed);
+    g_prof_cap.store(capacity, std::memory_order_relaxed);
+    return MOE_OK;
+}
+
 extern "C" moe_status moe_decompose_greedy(const int32_t* mats, int B, int N, int kmax, int flags, uint8_t* perms,
                                            int32_t* durations, int32_t* counts, int32_t* residual, uint64_t* hashes,
                                            void* hip_stream) {
     moe_status st = check_args(mats, B, N, kmax, counts);
     if (st != MOE_OK) return st;
+    if ((flags & MOE_DECOMP_RESIDUAL_I32) && (flags & MOE_DECOMP_RESIDUAL_U16)) return MOE_ERR_INVALID_ARG;
     if (B == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)hip_stream;
-    const bool narrow = (flags & MOE_DECOMP_ENTRIES_U16) != 0;
-    const size_t lds = (size_t)N * N * (narrow ? sizeof(uint16_t) : sizeof(int32_t));
+    // Residual in 16 bits where the entries allow it: half the LDS per matrix, so more wavefronts share a compute unit.
+    // That pays when LDS, not the number of matrices, limits how many are in flight: matrices of more than 64 ranks
+    // (64 KiB each in 32 bits: two per compute unit) in batches that fill the chip more than twice over.  A matrix
+    // with an entry of 65536 or more is marked by the 16-bit pass and decomposed by a second launch with the 32-bit
+    // residual, in which all other workgroups exit at once.
+    bool narrow = N > 64 && B > 2 * compute_units();
+    if (flags & MOE_DECOMP_RESIDUAL_I32) narrow = false;
+    if (flags & MOE_DECOMP_RESIDUAL_U16) narrow = true;
+    const int kflags = flags & MOE_DECOMP_ZERO_DIAGONAL;
+    unsigned long long* prof = g_prof.load(std::memory_order_relaxed);
+    const int prof_cap = g_prof_cap.load(std::memory_order_relaxed);
+    const size_t lds32 = (size_t)N * N * sizeof(int32_t);
+    auto wide = N <= 16 ? greedy_kernel<1, int32_t, 1> : N <= 32 ? greedy_kernel<1, int32_t, 2>
+              : N <= 64 ? greedy_kernel<1, int32_t, 4> : greedy_kernel<2, int32_t, 4>;
+    if (narrow) {
+        auto kern = N <= 16 ? greedy_kernel<1, uint16_t, 1> : N <= 32 ? greedy_kernel<1, uint16_t, 2>
+                  : N <= 64 ? greedy_kernel<1, uint16_t, 4> : greedy_kernel<2, uint16_t, 4>;
+        moe::LaunchScope k("greedy_kernel", s);
+        hipLaunchKernelGGL(kern, dim3(B), dim3(MOE_WAVE), lds32 / 2, s, mats, N, kmax, kflags, perms, durations, counts, residual,
+                           (unsigned long long*)hashes, prof, prof_cap);
+        st = k.done();
+        if (st != MOE_OK) return st;
+        moe::LaunchScope k2("greedy_redo_kernel", s);
+        hipLaunchKernelGGL(wide, dim3(B), dim3(MOE_WAVE), lds32, s, mats, N, kmax, kflags | REDO_MARKED, perms, durations, counts,
+                           residual, (unsigned long long*)hashes, prof, prof_cap);
+        return k2.done();
+    }
     moe::LaunchScope k("greedy_kernel", s);
-    auto kern = N <= 16   ? (narrow ? greedy_kernel<1, uint16_t, 1> : greedy_kernel<1, int32_t, 1>)
-                : N <= 32 ? (narrow ? greedy_kernel<1, uint16_t, 2> : greedy_kernel<1, int32_t, 2>)
-                : N <= 64 ? (narrow ? greedy_kernel<1, uint16_t, 4> : greedy_kernel<1, int32_t, 4>)
-                          : (narrow ? greedy_kernel<2, uint16_t, 4> : greedy_kernel<2, int32_t, 4>);
-    hipLaunchKernelGGL(kern, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts, residual,
-                       (unsigned long long*)hashes);
+    hipLaunchKernelGGL(wide, dim3(B), dim3(MOE_WAVE), lds32, s, mats, N, kmax, kflags, perms, durations, counts, residual,
+                       (unsigned long long*)hashes, prof, prof_cap);
     return k.done();
 }
 
@@ -1134,7 +1207,7 @@ extern "C" moe_status moe_decompose_bvn(const int32_t* mats, int B, int N, int k
     moe::LaunchScope k("bvn_kernel", s);
     auto kern = N <= 32 ? bvn_kernel<1, false> : (N <= 64 ? bvn_kernel<1, true> : bvn_kernel<2, true>);
     hipLaunchKernelGGL(kern, dim3(B), dim3(MOE_WAVE), lds, s, mats, N, kmax, flags, perms, durations, counts, residual, pad_total,
-                       (unsigned long long*)hashes);
+                       (unsigned long long*)hashes, g_prof.load(std::memory_order_relaxed), g_prof_cap.load(std::memory_order_relaxed));
     return k.done();
 }
 

@@ -37,6 +37,17 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.moe_route_histogram(None, 1, 4, 4, 1, 6, None, None, None) == -1          # traffic missing
     assert L.moe_decompose_greedy(None, 1, 200, 4, 0, None, None, ctypes.c_void_p(8), None, None, None) == -1
     assert L.moe_decompose_greedy(ctypes.c_void_p(8), 1, 200, 4, 0, None, None, ctypes.c_void_p(8), None, None, None) == -2
+    # both pins of the residual width at once
+    assert L.moe_decompose_greedy(ctypes.c_void_p(8), 1, 4, 1, 2 | 4, None, None, ctypes.c_void_p(8), None, None, None) == -1
+    assert L.moe_decompose_profile(None, 3) == -1 and L.moe_decompose_profile(None, 0) == 0
+    assert L.moe_ffn_tile_override(100, 0) == -1 and L.moe_ffn_tile_override(0, 2) == -1 and L.moe_ffn_tile_override(0, 0) == 0
+    # a schedule too long for the built-in work area of the allocation-free slice table
+    assert L.moe_slice_table_static(ctypes.c_void_p(8), 8, 4, 1, 8, 0, ctypes.c_void_p(8), ctypes.c_void_p(8), ctypes.c_void_p(8),
+                                    ctypes.c_void_p(8), 70000, ctypes.c_void_p(8), None) == -3
+    # the FFN takes any number of rows below 2^31, but 32-bit offsets inside one expert's matrices
+    assert L.moe_expert_ffn_sliced(ctypes.c_void_p(4096), ctypes.c_void_p(8), 4, 1, 1, 1 << 16, 1 << 15, 0, ctypes.c_void_p(4096),
+                                   ctypes.c_void_p(4096), ctypes.c_void_p(4096), None, None, None, ctypes.c_void_p(4096),
+                                   None, 0, None) == -2
     assert L.moe_expert_ffn_sliced(ctypes.c_void_p(8), ctypes.c_void_p(8), 4, 1, 1, 100, 128, 0, ctypes.c_void_p(8),
                                    ctypes.c_void_p(8), ctypes.c_void_p(8), None, None, None, ctypes.c_void_p(8),
                                    None, 0, None) == -2                                  # d % 256 != 0

@@ -236,6 +236,29 @@ def activations(M: int, d: int, seed: int) -> np.ndarray:
     return out
 
 
+def ffn_weights_on_device(E_loc: int, d: int, f: int, seed: int, dtype: str, device, std: float = 0.02):
+    """Expert weights drawn and packed on `device` with torch (same distribution and formats as ffn_weights(), another
+    random stream): dict of w_gate, w_up [E_loc][f][d], w_down [E_loc][d][f] as bf16 tensors, or as uint8 E4M3 codes
+    plus float32 scales s_* per 128 x 128 block (scale = amax / 448).  For timing runs whose host copy is not needed."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed + 7919)
+    out = {}
+    for name, shape in (("gate", (E_loc, f, d)), ("up", (E_loc, f, d)), ("down", (E_loc, d, f))):
+        w = torch.randn(shape, dtype=torch.float32, device=device, generator=g) * std
+        if dtype == "bf16":
+            out["w_" + name] = w.to(torch.bfloat16)
+            continue
+        E, R, C = shape
+        blk = w.view(E, R // 128, 128, C // 128, 128)
+        scale = blk.abs().amax(dim=(2, 4)) / 448.0
+        scale = torch.where(scale == 0, torch.ones_like(scale), scale)
+        q = (blk / scale[:, :, None, :, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn)
+        out["w_" + name] = q.view(torch.uint8).view(E, R, C).contiguous()
+        out["s_" + name] = scale.contiguous()
+    return out
+
+
 def activations_on_device(M: int, d: int, seed: int, device):
     """x[M][d] ~ N(0,1) as a bf16 torch tensor drawn on `device` (for row counts whose host copy would take minutes to
     draw and gigabytes to hold); a checker reads back the rows it needs.  Seeded, but a different stream than
