@@ -654,6 +654,23 @@ def histogram_and_sinkhorn_extras(moe, torch, np, workloads, dev):
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
     nbytes = ids.numel() * 4 + tr.numel() * 4 + cn.numel() * 4
+    del ids, tr, cn
+    # combine at the source rank: weighted top-8 sum over 7168-wide rows (the shape of the 64-rank configuration), 32 Ki tokens
+    T, topk, d = 32768, 8, 7168
+    yy = torch.empty((T * topk, d), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+    row_of = torch.randperm(T * topk, device=dev, generator=g).to(torch.int32).view(T, topk)
+    gate = torch.rand((T, topk), device=dev, generator=g)
+    oo = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    moe.moe_combine_topk_sum(yy, row_of, gate, out=oo)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        moe.moe_combine_topk_sum(yy, row_of, gate, out=oo)
+    torch.cuda.synchronize()
+    dtc = (time.perf_counter() - t0) / reps
+    cbytes = (topk + 1) * 2 * d * T + 8 * T * topk
+    out["combine_topk_sum"] = {"tokens": T, "topk": topk, "d": d, "bytes": cbytes, "us": dtc * 1e6, "GB_per_s": cbytes / dtc / 1e9,
+                               "frac_hbm_peak": cbytes / dtc / 1e9 / HBM_PEAK_GBS, "bound": "hbm"}
     out["histogram_64_layers"] = {"bytes": nbytes, "GB_per_s": nbytes / dt / 1e9, "frac_hbm_peak": nbytes / dt / 1e9 / HBM_PEAK_GBS, "bound": "hbm"}
     return out
 

@@ -249,6 +249,24 @@ moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t* offsets, i
                                         void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_combine_topk_sum -- Section 2.1 (combine): the expert results travel back to the rank that
+ * owns the tokens, where each token's output is the router-weighted sum over its topk experts:
+ *     out[t] = sum_{j < topk} gate[t][j] * y[row_of[t][j]]
+ * accumulated in fp32 in slot order j = 0, 1, ... (one fused multiply-add per term), rounded to bf16
+ * once.
+ *   y        in   bf16 [R][d]       expert results, one row per (token, expert) assignment, any order
+ *   row_of   in   int32 [T][topk]   row of y that holds the result of token t's slot j; a value
+ *                                   outside [0, R) (e.g. -1: dropped assignment) contributes nothing
+ *   gate     in   float [T][topk]   router weights; NULL = 1 (e.g. when the weight was already applied
+ *                                   by moe_expert_ffn_sliced_mapped's row_gate)
+ *   out      out  bf16 [T][d], overwritten (a token with no live assignment gets zeros)
+ * Limits: d % 8 == 0, T * topk < 2^31; y and out 16-byte aligned.  HBM bound: (topk + 1) * 2 * d
+ * bytes per token.
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_combine_topk_sum(const void* y, const int32_t* row_of, const float* gate, int T, int topk, int d,
+                                int R, void* out, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * moe_ffn_tile_override -- test and measurement hook, not meant for production callers.  The FFN
  * calls choose the height of their row blocks (64, 128 or 256 rows) and the kernel family (one
  * whose tile shape adapts to ragged group ends, or fixed-shape tiles) from the shape of the

@@ -31,7 +31,7 @@ EXPORTS = [
     "moe_slice_table", "moe_ffn_workspace_bytes", "moe_ffn_expanded_weights_bytes", "moe_expert_ffn_sliced", "moe_kernel_timing_enable",
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped", "moe_ffn_tile_override",
-    "moe_slice_table_static", "moe_decompose_profile",
+    "moe_slice_table_static", "moe_decompose_profile", "moe_combine_topk_sum",
 ]
 
 _lib = None
@@ -107,6 +107,8 @@ def load():
     L.moe_ffn_expanded_weights_bytes.restype = sz
     L.moe_expert_ffn_sliced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moe_expert_ffn_sliced.restype = ci
+    L.moe_combine_topk_sum.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+    L.moe_combine_topk_sum.restype = ci
     L.moe_ffn_tile_override.argtypes = [ci, ci]
     L.moe_ffn_tile_override.restype = ci
     L.moe_kernel_timing_enable.argtypes = [ci]
@@ -364,6 +366,24 @@ def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, 
                                         _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(y), _ptr(workspace),
                                         workspace.numel(), _stream()), "moe_expert_ffn_sliced")
     return y
+
+
+def moe_combine_topk_sum(y, row_of, gate=None, out=None):
+    """y bf16 [R][d], row_of int32 [T][topk], gate float32 [T][topk] or None -> out bf16 [T][d]."""
+    import torch
+    _dev_check(y, torch.bfloat16, "y")
+    _dev_check(row_of, torch.int32, "row_of")
+    _dev_check(gate, torch.float32, "gate")
+    R, d = y.shape
+    T, topk = row_of.shape
+    if gate is not None and tuple(gate.shape) != (T, topk):
+        raise MoeError("gate must have the shape of row_of")
+    if out is None:
+        out = torch.empty((T, d), dtype=torch.bfloat16, device=y.device)
+    _dev_check(out, torch.bfloat16, "out")
+    _check(load().moe_combine_topk_sum(_ptr(y), _ptr(row_of), _ptr(gate), T, topk, d, R, _ptr(out), _stream()),
+           "moe_combine_topk_sum")
+    return out
 
 
 def moe_ffn_tile_override(tile_rows: int = 0, fixed_shape: bool = False):

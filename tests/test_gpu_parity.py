@@ -655,6 +655,79 @@ def test_ffn_mapped(lib, dtype, tile_rows):
         lib.moe_ffn_tile_override()
 
 
+# ------------------------------------------------------------------------------ combine
+def combine_tolerance(y_bits, row_of, gate, ref):
+    """fp32 accumulation of topk terms (2^-24 of the terms' magnitudes each) and one rounding to bf16 (2^-9 of the
+    result): |out - ref| <= 2^-8 |ref| + 2^-20 sum_j |gate * y| elementwise, with room to spare."""
+    y = np.abs(oracle.decode_bf16(y_bits))
+    live = (row_of >= 0) & (row_of < y.shape[0])
+    g = np.ones(row_of.shape, dtype=np.float64) if gate is None else np.abs(gate.astype(np.float64))
+    mag = (y[np.clip(row_of, 0, y.shape[0] - 1)] * (g * live)[:, :, None]).sum(axis=1)
+    return 2.0 ** -8 * np.abs(ref) + 2.0 ** -20 * mag + 1e-30
+
+
+@pytest.mark.parametrize("T,topk,d,R", [(1, 1, 8, 1), (37, 2, 256, 80), (50, 3, 2056, 160), (19, 8, 4096, 200), (300, 4, 7168, 1200),
+                                       (11, 6, 512, 70), (5, 5, 16, 40)])
+@pytest.mark.parametrize("gated", [True, False])
+def test_combine_topk_sum(lib, T, topk, d, R, gated):
+    say("combine", T, topk, d, R, gated)
+    rng = np.random.default_rng(T * 31 + topk)
+    y = workloads.activations(R, d, seed=T + d)
+    row_of = rng.integers(0, R, size=(T, topk)).astype(np.int32)
+    if T > 4:
+        row_of[1, 0] = -1                                              # a dropped assignment
+        row_of[2, :] = -1                                              # a token that lost every expert
+        row_of[3, topk - 1] = R + 5                                    # past the end: ignored as well
+    gate = rng.uniform(0.0, 1.0, size=(T, topk)).astype(np.float32) if gated else None
+    out0 = torch.full((T, d), 3.0, dtype=torch.bfloat16, device=DEV)
+    out = lib.moe_combine_topk_sum(dev_bf16(y), dev(row_of), dev(gate) if gated else None, out=out0)
+    torch.cuda.synchronize()
+    ref = oracle.combine_topk_sum(y, row_of, gate)
+    got = oracle.decode_bf16(host_bf16_bits(out))
+    assert (np.abs(got - ref) <= combine_tolerance(y, row_of, gate, ref)).all(), np.abs(got - ref).max()
+    if T > 4:
+        assert not got[2].any()
+
+
+def test_moe_layer_dispatch_compute_combine(lib):
+    """One whole layer on one GPU (every expert local): tokens -> one row per (token, expert) assignment -> slice table
+    with row map -> FFN with fused gather, scatter and router weight -> weighted top-k sum per token; against
+    sum_j gate[t][j] * FFN_{e(t,j)}(x_t) evaluated by the oracle."""
+    say("moe layer: dispatch -> compute -> combine")
+    T, E, topk, d, f = 3000, 4, 2, 512, 384
+    ids = workloads.route_topk(1, T, E, topk, 1.0, seed=77)
+    rng = np.random.default_rng(78)
+    gate = rng.uniform(0.1, 1.0, size=(T, topk)).astype(np.float32)
+    W = workloads.ffn_weights(E, d, f, seed=79)
+    x_tok = workloads.activations(T, d, seed=80)
+    x_arr = np.repeat(x_tok, topk, axis=0)                               # arrival order: (token, slot)
+    d_ids = dev(ids)
+    traffic, _ = lib.moe_route_histogram(d_ids, E)
+    kmax = 2
+    sched = lib.moe_decompose_greedy(traffic.unsqueeze(0), kmax, zero_diag=True)
+    M = T * topk
+    offsets, arr, asg = lib.moe_slice_table_rows(d_ids, E, 0, traffic, sched["perms"][0], sched["durations"][0], sched["counts"], kmax, M)
+    torch.cuda.synchronize()
+    assert int(offsets[-1].item()) == M and torch.equal(arr, asg)        # one source: arrival index = assignment index
+    row_gate = dev(gate.reshape(-1))[arr.long()].contiguous()            # router weight of the assignment behind each schedule row
+    y_arr = lib.moe_expert_ffn_sliced_mapped(dev_bf16(x_arr), offsets, kmax + 2, E, row_map=arr, row_gate=row_gate, **upload_weights(W))
+    row_of = np.arange(M, dtype=np.int32).reshape(T, topk)
+    out = lib.moe_combine_topk_sum(y_arr, dev(row_of))
+    torch.cuda.synchronize()
+    # oracle: every assignment through its expert, then the weighted sum
+    off_e = np.zeros(E + 1, dtype=np.int32)
+    flat = ids.reshape(-1)
+    order = np.argsort(flat, kind="stable")
+    off_e[1:] = np.cumsum(np.bincount(flat, minlength=E))
+    y_sorted = oracle.expert_ffn_sliced(x_arr[order], off_e, E, W)
+    y_asg = np.empty_like(y_sorted)
+    y_asg[order] = y_sorted
+    ref = (y_asg.reshape(T, topk, d) * gate.astype(np.float64)[:, :, None]).sum(axis=1)
+    got = oracle.decode_bf16(host_bf16_bits(out))
+    err = float(np.abs(got - ref).max() / np.abs(ref).max())
+    check_ffn_error(err, "bf16", "layer output, %d tokens" % T)
+
+
 def sample_rows(off, per_group, seed=1, blocks=()):
     """Every non-empty group contributes its first and last rows plus a random sample; `blocks` adds every row of the
     given (first row, end row) stretches."""
