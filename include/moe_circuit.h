@@ -268,17 +268,20 @@ moe_status moe_combine_topk_sum(const void* y, const int32_t* row_of, const floa
 
 /* ---------------------------------------------------------------------------------------------
  * moe_ffn_tile_override -- test and measurement hook, not meant for production callers.  The FFN
- * calls choose the height of their row blocks (64, 128 or 256 rows) and the kernel family (one
- * whose tile shape adapts to ragged group ends, or fixed-shape tiles) from the shape of the
- * schedule; this call pins either choice for all following moe_expert_ffn_sliced(_mapped) calls of
+ * calls choose the height of their row blocks (64, 128 or 256 rows), the kernel family (one
+ * whose tile shape adapts to ragged group ends, or fixed-shape tiles) and the order in which the
+ * output tiles are walked from the shape of the schedule; this call pins any of these choices for all following moe_expert_ffn_sliced(_mapped) calls of
  * the process, so that every kernel can be driven on small inputs and timed on any input.
  *   tile_rows    0 = chosen per call (the default), else 64, 128 or 256
  *   fixed_shape  0 = chosen per call (the default), 1 = always the fixed-shape kernels
+ *   panel_groups 0 = chosen per call (the default), else the number of column groups (of up to 8
+ *                column tiles) the tile walk finishes for all rows before it moves on to the next
+ *                columns (a large value = all columns in one sweep per row group)
  * Process-wide and not synchronised with FFN calls running on other threads.  Results of any
  * choice agree within the rounding of the fp32 sums (the order of the additions differs).
  * Returns MOE_ERR_INVALID_ARG for other values (nothing changes then).
  * ------------------------------------------------------------------------------------------- */
-moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape);
+moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape, int panel_groups);
 
 /* ---------------------------------------------------------------------------------------------
  * moe_makespan_model -- Section 5 (Setup: "Execution time"), host-side.  Analytic completion time

@@ -39,6 +39,7 @@ struct FfnArgs {
     int d, f;
     const int32_t* row_map;            // [M] or null: row m of the schedule is row row_map[m] of x and of y
     const float* row_gate;             // [M] or null: y row is scaled by row_gate[m]
+    int panel1, panel2;                // column groups per panel of the tile walk, phase 1 / phase 2 (see TileGeom)
 };
 // row of x that schedule row m reads (phase 1) / row of y it writes (phase 2)
 __device__ __forceinline__ int mapped_row(const FfnArgs& a, int m) { return a.row_map ? a.row_map[m] : m; }
@@ -176,22 +177,37 @@ __device__ __forceinline__ u32x4 dequant8(u32x2 codes, float scale) {
 // walking its own chunks of neighbouring tiles so that the workgroups sharing an L2 also share
 // operand slabs; a workgroup whose queue runs dry takes from the others.
 
-struct TileGeom {                      // how tiles are grouped into chunks
-    int nblocks, NT, NCG, CN, RB, nchunks;
-    __device__ __forceinline__ void init(int nblocks_, int NT_) {
+struct TileGeom {                      // how tiles are grouped into chunks, and the order in which the chunks are walked
+    int nblocks, NT, NCG, CN, RB, NRG, W, nchunks;
+    __device__ __forceinline__ void init(int nblocks_, int NT_, int panel) {
         nblocks = nblocks_; NT = NT_;
         NCG = (NT + 7) / 8;                        // column groups of at most 8 (11 -> 2 x 6)
         CN = (NT + NCG - 1) / NCG;
         RB = 32 / CN < 1 ? 1 : 32 / CN;            // about 32 tiles per chunk
-        nchunks = ((nblocks + RB - 1) / RB) * NCG;
+        NRG = (nblocks + RB - 1) / RB;             // row groups
+        W = panel < 1 ? 1 : (panel > NCG ? NCG : panel);      // column groups per panel
+        nchunks = NRG * NCG;
     }
-    // ticket k of queue x -> tile; returns 1 = valid, 0 = hole in the padded grid, -1 = queue exhausted
+    // ticket k of queue x -> tile; returns 1 = valid, 0 = hole in the padded grid, -1 = queue exhausted.
+    // Chunks are walked panel by panel: inside a panel of W column groups the row groups are the outer loop, so the
+    // panel's weights are touched again after one row group's worth of other traffic and stay in the memory-side cache
+    // while the activations stream past; W = NCG (one panel) when an expert's weights are small.
     __device__ __forceinline__ int decode(int x, int k, int& blk, int& nt) const {
         const int chs = RB * CN;
         const int c = (k / chs) * 8 + x, j = k % chs;
         if (c >= nchunks) return -1;
-        blk = (c / NCG) * RB + j / CN;
-        nt = (c % NCG) * CN + j % CN;
+        const int full = (NCG / W) * W;            // column groups inside whole panels
+        const int c0 = NRG * full;
+        int rg, cg;
+        if (c < c0) {
+            const int per = NRG * W, p = c / per, rem = c - p * per;
+            rg = rem / W; cg = p * W + rem - rg * W;
+        } else {
+            const int wl = NCG - full, rem = c - c0;
+            rg = rem / wl; cg = full + rem - rg * wl;
+        }
+        blk = rg * RB + j / CN;
+        nt = cg * CN + j % CN;
         return (blk < nblocks && nt < NT) ? 1 : 0;
     }
 };
@@ -245,7 +261,7 @@ void ffn_gemm_kernel(FfnArgs a) {
     const int K = PHASE == 1 ? a.d : a.f;
     const int KT = K / BK;
     TileGeom geom;
-    geom.init(a.plan[0].x, PHASE == 1 ? a.f / 128 : a.d / BN);
+    geom.init(a.plan[0].x, PHASE == 1 ? a.f / 128 : a.d / BN, PHASE == 1 ? a.panel1 : a.panel2);
     int* queues = (int*)(a.plan + (PHASE == 1 ? 1 : 3));
     const int my_xcd = blockIdx.x & 7;
 
@@ -568,7 +584,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
     const int K = PHASE == 1 ? a.d : a.f;
     const int NU = PHASE == 1 ? a.f / 128 : a.d / 256;          // column units
     TileGeom geom;
-    geom.init(a.plan[0].x, NU);
+    geom.init(a.plan[0].x, NU, PHASE == 1 ? a.panel1 : a.panel2);
     int* queues = (int*)(a.plan + (PHASE == 1 ? 1 : 3));
     const int my_xcd = blockIdx.x & 7;
 
@@ -963,6 +979,7 @@ size_t h_bytes(int M, int f) { return (((size_t)M * f * 2) + 255) & ~(size_t)255
 
 std::atomic<int> g_force_rows{0};          // moe_ffn_tile_override: 0 = rows per tile chosen per call, else 64 / 128 / 256
 std::atomic<int> g_force_fixed{0};         //                        1 = never the adaptive-shape kernels
+std::atomic<int> g_force_panel{0};         //                        0 = panel width of the tile walk chosen per call, else column groups per panel
 std::atomic<int> g_num_cus[64];            // compute units of device d (0 = not asked yet)
 int num_cus() {
     int dev = 0, n = 0;
@@ -973,6 +990,19 @@ int num_cus() {
         g_num_cus[dev].store(n, std::memory_order_relaxed);
     }
     return n;
+}
+
+// Column groups per panel of the tile walk.  The walk sweeps a panel's weights once per row group; as long as one
+// expert's weights of the phase (plus a row group's activations and results) fit the 256 MB memory-side cache with room
+// to spare, one panel holds all column groups.  Beyond that every sweep would evict what the next one needs (a cyclic
+// pattern just above an LRU cache's size misses every time), so the columns are split into panels of about 64 MB and
+// the activations are streamed once per panel instead.
+int panel_width(int units, size_t expert_weight_bytes, size_t unit_bytes) {
+    const int ncg = (units + 7) / 8, cn = (units + ncg - 1) / ncg;
+    if (expert_weight_bytes <= ((size_t)128 << 20)) return ncg;
+    const size_t group_bytes = (size_t)cn * unit_bytes;
+    const int w = (int)(((size_t)64 << 20) / (group_bytes ? group_bytes : 1));
+    return w < 1 ? 1 : (w > ncg ? ncg : w);
 }
 
 // Tile shapes.  ROWS = rows per tile:
@@ -1041,11 +1071,13 @@ extern "C" size_t moe_ffn_workspace_bytes(int M, int d, int f) {
     return h_bytes(M, f) + (size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4);
 }
 
-extern "C" moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape) {
+extern "C" moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape, int panel_groups) {
     if (tile_rows != 0 && tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return MOE_ERR_INVALID_ARG;
     if (fixed_shape != 0 && fixed_shape != 1) return MOE_ERR_INVALID_ARG;
+    if (panel_groups < 0) return MOE_ERR_INVALID_ARG;
     g_force_rows.store(tile_rows, std::memory_order_relaxed);
     g_force_fixed.store(fixed_shape, std::memory_order_relaxed);
+    g_force_panel.store(panel_groups, std::memory_order_relaxed);
     return MOE_OK;
 }
 
@@ -1114,6 +1146,9 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     a.plan = plan;
     a.d = d; a.f = f;
     a.row_map = row_map; a.row_gate = row_gate;
+    a.panel1 = panel_width(f / 128, (size_t)2 * d * f * 2, (size_t)256 * d * 2);
+    a.panel2 = panel_width(d / 256, (size_t)d * f * 2, (size_t)256 * f * 2);
+    if (const int forced = g_force_panel.load(std::memory_order_relaxed)) a.panel1 = a.panel2 = forced;
     {
         moe::LaunchScope k("ffn_plan_kernel", s);
         hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, (int)G, E_loc, M, bm,

@@ -534,6 +534,24 @@ def test_ffn_many_tiles_per_workgroup_all_rows(lib, dtype, tile_rows, fixed):
         lib.moe_ffn_tile_override()
 
 
+@pytest.mark.parametrize("tile_rows,fixed,panel", [(0, False, 1), (0, False, 2), (256, True, 2), (128, False, 1)])
+def test_ffn_panel_walk_all_rows(lib, tile_rows, fixed, panel):
+    """The tile walk in column panels (what a call chooses by itself only for experts whose weights outgrow the
+    memory-side cache): 18 column units in 3 groups, walked 1 or 2 groups at a time; every row compared."""
+    say("ffn panel walk", tile_rows, fixed, panel)
+    E_loc, d, f, S, M = 2, 512, 2304, 3, 12000
+    W = workloads.ffn_weights(E_loc, d, f, seed=25)
+    x = workloads.activations(M, d, seed=26)
+    offsets = workloads.random_offsets(S * E_loc, M, seed=27)
+    lib.moe_ffn_tile_override(tile_rows, fixed, panel)
+    try:
+        y = lib.moe_expert_ffn_sliced(dev_bf16(x), dev(offsets), S, E_loc, **upload_weights(W))
+        torch.cuda.synchronize()
+    finally:
+        lib.moe_ffn_tile_override()
+    check_ffn_error(ffn_error(host_bf16_bits(y), oracle.expert_ffn_sliced(x, offsets, E_loc, W), offsets), "bf16", "all %d rows" % M)
+
+
 @pytest.mark.parametrize("S,E_loc,tile_rows", [(375, 4, 0), (375, 4, 256), (1250, 4, 0), (1250, 4, 256), (5000, 1, 128)])
 def test_ffn_thousands_of_groups_all_rows(lib, S, E_loc, tile_rows):
     """More (slice, expert) groups than the planning workgroup has threads (a full BvN schedule at 64 ranks has 3972
