@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["tiny", "c2", "c3", "c4"])
+    ap.add_argument("--ffn-kernels", type=int, default=0, choices=[0, 1, 2],
+                    help="moe_ffn_tile_override's kernel choice: 0 = the library's own (both phases in one launch where it applies), "
+                         "1 = fixed-shape kernels, 2 = adaptive-shape kernels with one launch per phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -70,12 +73,35 @@ def kernel_key(name):
         return "ffn_gemm1_kernel"
     if "ffn_adaptive_kernel<2" in name or "ffn_gemm_kernel<2," in name:
         return "ffn_gemm2_kernel"
+    if "ffn_fused_kernel" in name:
+        return "ffn_fused_kernel"
     if "copyBuffer" in name:
         return "copy"
     for k in ("bvn_kernel", "greedy_kernel", "st_count_kernel", "st_scan_kernel", "ffn_plan_kernel", "hist_kernel", "ffn_expand_fp8_kernel"):
         if k in name:
             return k
     return None
+
+
+FFN_KERNELS = ("ffn_fused_kernel", "ffn_gemm1_kernel", "ffn_gemm2_kernel")
+
+
+def ffn_kernel_work(cfg, M):
+    """Algorithmic flop and bytes per launch of the FFN matrix kernels (phase 1 = gemm1, phase 2 = gemm2, fused = both)."""
+    xb, hb = M * cfg.d * 2.0, M * cfg.f * 2.0
+    wb = cfg.E_loc * cfg.d * cfg.f * 2.0                                       # one of the three weight matrices, all experts (bf16)
+    unit = cfg.d * cfg.f * float(M)
+    return {"ffn_gemm1_kernel": {"flop": 4 * unit, "bytes": xb + 2 * wb + hb, "what": "x and gate/up weights read, h written"},
+            "ffn_gemm2_kernel": {"flop": 2 * unit, "bytes": hb + wb + xb, "what": "h and down weights read, y written"},
+            "ffn_fused_kernel": {"flop": 6 * unit, "bytes": 2 * xb + 3 * wb + 2 * hb, "what": "x and all weights read, h written and read, y written"}}
+
+
+def profile_suffix(args):
+    return "_per_phase" if args.ffn_kernels == 2 else ("_fixed_shape" if args.ffn_kernels == 1 else "")
+
+
+def bench_flags(args):
+    return " --ffn-kernels %d" % args.ffn_kernels if args.ffn_kernels else ""
 
 
 def workload_shape(workload):
@@ -87,11 +113,12 @@ def workload_shape(workload):
     return cfg, M
 
 
-def summarize_counters(workload, fetch_csv, write_csv):
-    """FETCH_SIZE / WRITE_SIZE (KiB per dispatch) of the two FFN kernels, scaled by what the same counter reads for the
+def summarize_counters(args, fetch_csv, write_csv):
+    """FETCH_SIZE / WRITE_SIZE (KiB per dispatch) of the FFN matrix kernels, scaled by what the same counter reads for the
     256 MiB calibration copy; stored with the SHA-256 of the kernel source it was measured on."""
     import collections
     import csv
+    workload = args.workload
 
     def averages(path):
         acc = collections.defaultdict(list)
@@ -103,55 +130,59 @@ def summarize_counters(workload, fetch_csv, write_csv):
 
     f, w = averages(fetch_csv), averages(write_csv)
     cal_f, cal_w = 262144.0 / f["copy"], 262144.0 / w["copy"]
+    cfg, M = workload_shape(workload)
+    work = ffn_kernel_work(cfg, M)
     detail = {}
-    for k in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
-        rb, wb = f[k] * cal_f * 1024, w[k] * cal_w * 1024
-        detail[k] = {"read_bytes": rb, "write_bytes": wb, "total_bytes": rb + wb}
+    for k in FFN_KERNELS:
+        if k in f and k in w:
+            rb, wb = f[k] * cal_f * 1024, w[k] * cal_w * 1024
+            detail[k] = {"read_bytes": rb, "write_bytes": wb, "total_bytes": rb + wb, "algorithmic_bytes": work[k]["bytes"],
+                         "ratio": (rb + wb) / work[k]["bytes"]}
     rel = "paper_2605_26845_amd/csrc/ffn.hip"
     sha = code_digest(os.path.join(ROOT, rel))
-    base = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic" % workload)
-    json.dump({"kernel": "ffn_gemm1_kernel", "workload": workload, "source_sha256": {rel: sha},
-               "traffic_bytes_per_launch": detail["ffn_gemm1_kernel"]["total_bytes"], "detail": detail,
+    base = os.path.join(ROOT, "profiles", "ffn_%s%s_hbm_traffic" % (workload, profile_suffix(args)))
+    json.dump({"workload": workload, "source_sha256": {rel: sha}, "detail": detail,
                "calibration_factor": {"FETCH_SIZE": cal_f, "WRITE_SIZE": cal_w},
-               "see": "profiles/ffn_%s_hbm_traffic.md" % workload}, open(base + ".json", "w"), indent=1)
-    lines = ["# HBM-side byte counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels (gemm1 = phase 1: gate/up + SwiGLU)" % workload,
+               "see": os.path.basename(base) + ".md"}, open(base + ".json", "w"), indent=1)
+    lines = ["# HBM-side byte counters (rocprofv3 --pmc), bench.py workload %s, the FFN matrix kernels" % workload,
              "", "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box, one counter per run; then the summary, no GPU needed):", ""]
     rel_csv = [os.path.relpath(os.path.abspath(c), ROOT) for c in (fetch_csv, write_csv)]      # as given on the command line
     for c, path in zip(("FETCH_SIZE", "WRITE_SIZE"), rel_csv):
-        lines.append("    rocprofv3 --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s --steps 10 "
-                     "--warmup 2 --no-extras --no-cpu-baseline --calibration-copy" % (c, os.path.dirname(path), workload))
-    lines += ["    python3 bench.py --workload %s --summarize-counters %s %s" % (workload, rel_csv[0], rel_csv[1]), "",
+        lines.append("    rocprofv3 --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s%s --steps 10 "
+                     "--warmup 2 --no-extras --no-cpu-baseline --calibration-copy" % (c, os.path.dirname(path), workload, bench_flags(args)))
+    lines += ["    python3 bench.py --workload %s%s --summarize-counters %s %s" % (workload, bench_flags(args), rel_csv[0], rel_csv[1]), "",
               "Calibration: the plain device-to-device copy of 256 MiB (`--calibration-copy`, the largest __amd_rocclr_copyBuffer dispatch) reads",
               "FETCH_SIZE = %.1f and WRITE_SIZE = %.1f for 262144 KiB each way -> scale factors %.4f (fetch) and %.4f (write)."
               % (f["copy"], w["copy"], cal_f, cal_w), "",
-              "| kernel | FETCH_SIZE avg | WRITE_SIZE avg | scaled read MB | scaled write MB | total MB per launch |", "|---|---|---|---|---|---|"]
-    for k in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
-        d = detail[k]
-        lines.append("| %s | %.0f | %.0f | %.1f | %.1f | %.1f |" % (k, f[k], w[k], d["read_bytes"] / 1e6, d["write_bytes"] / 1e6, d["total_bytes"] / 1e6))
-    cfg, M = workload_shape(workload)
-    xb, wb_, hb = M * cfg.d * 2, 2 * cfg.E_loc * cfg.d * cfg.f * 2, M * cfg.f * 2
-    lines += ["", "Algorithmic bytes of ffn_gemm1_kernel at this workload (M=%d, d=%d, f=%d, %d experts): x %.1f MB + gate/up weights %.1f MB read,"
-              % (M, cfg.d, cfg.f, cfg.E_loc, xb / 1e6, wb_ / 1e6),
-              "h %.1f MB written = %.1f MB; ffn_gemm2_kernel: h %.1f MB + down weights %.1f MB read, y %.1f MB written = %.1f MB."
-              % (hb / 1e6, (xb + wb_ + hb) / 1e6, hb / 1e6, wb_ / 2e6, xb / 1e6, (hb + wb_ / 2 + xb) / 1e6),
-              "The fetch counter sits between the L2 and the fabric: it also counts reads served by the 256 MB memory-side cache.",
-              "The stored figure (`.json`) carries the SHA-256 of ffn.hip (comments and blank space removed) it was measured on; bench.py reports it as `roofline.traffic` only while that matches.", ""]
+              "| kernel | FETCH_SIZE avg | WRITE_SIZE avg | scaled read MB | scaled write MB | total MB per launch | algorithmic MB | ratio |", "|---|---|---|---|---|---|---|---|"]
+    for k, d in detail.items():
+        lines.append("| %s | %.0f | %.0f | %.1f | %.1f | %.1f | %.1f | %.2f |" % (k, f[k], w[k], d["read_bytes"] / 1e6, d["write_bytes"] / 1e6,
+                                                                         d["total_bytes"] / 1e6, d["algorithmic_bytes"] / 1e6, d["ratio"]))
+    lines += ["", "Algorithmic bytes at this workload (M=%d rows, d=%d, f=%d, %d experts, bf16):" % (M, cfg.d, cfg.f, cfg.E_loc)]
+    lines += ["- %s: %s = %.1f MB" % (k, work[k]["what"], work[k]["bytes"] / 1e6) for k in detail]
+    lines += ["The fetch counter sits between a die's L2 and the fabric: it also counts reads served by the 256 MB memory-side cache, and an operand",
+              "strip shared by the tiles of two dies is fetched once per die.",
+              "The stored figures (`.json`) carry the SHA-256 of ffn.hip (comments and blank space removed) they were measured on; bench.py reports",
+              "the dominant kernel's as `roofline.traffic` only while that matches.", ""]
     open(base + ".md", "w").write("\n".join(lines))
     print(base + ".md")
 
 
-def summarize_kernel_stats(workload, stats_csv):
+def summarize_kernel_stats(args, stats_csv):
     import csv
+    workload = args.workload
     cfg, M = workload_shape(workload)
+    work = ffn_kernel_work(cfg, M)
     rel = os.path.relpath(os.path.abspath(stats_csv), ROOT)
     out_dir, prefix = os.path.dirname(rel), os.path.basename(rel).replace("_kernel_stats.csv", "")
     lines = ["# rocprofv3 kernel-trace summary: bench.py, workload %s (N=%d, %d experts, top-%d, %d tokens/rank; %d experts d=%d f=%d; hottest rank: %d rows)"
              % (workload, cfg.N, cfg.E, cfg.topk, cfg.T, cfg.E_loc, cfg.d, cfg.f, M), "",
              "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box; then the summary, no GPU needed):", "",
-             "    rocprofv3 --kernel-trace --stats --output-format csv -d %s -o %s -- python3 bench.py --workload %s --steps 20 --no-extras --no-cpu-baseline"
-             % (out_dir, prefix, workload),
-             "    python3 bench.py --workload %s --summarize-kernel-stats %s" % (workload, rel), "",
-             "(library kernels only, times in microseconds)", "",
+             "    rocprofv3 --kernel-trace --stats --output-format csv -d %s -o %s -- python3 bench.py --workload %s%s --steps 20 --no-extras --no-cpu-baseline"
+             % (out_dir, prefix, workload, bench_flags(args)),
+             "    python3 bench.py --workload %s%s --summarize-kernel-stats %s" % (workload, bench_flags(args), rel), "",
+             "(library kernels only, times in microseconds; the run also holds bench.py's passes with one event pair per kernel and, unless",
+             "--ffn-kernels is given, with one launch per FFN phase: the phase kernels below come from that pass)", "",
              "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
     avg = {}
     for row in csv.DictReader(open(stats_csv)):
@@ -162,17 +193,16 @@ def summarize_kernel_stats(workload, stats_csv):
         lines.append("| %s | %s | %.1f | %.1f | %.1f | %s |" % (name, row["Calls"], float(row["AverageNs"]) / 1e3, float(row["MinNs"]) / 1e3,
                                                             float(row["MaxNs"]) / 1e3, row["Percentage"]))
         avg[key] = float(row["AverageNs"]) / 1e3
-    f1, f2 = 4.0 * cfg.d * cfg.f * M, 2.0 * cfg.d * cfg.f * M
-    lines += ["", "bench.py reports the phase-1 kernel (gate/up projections + SwiGLU) as ffn_gemm1_kernel and the phase-2 kernel (down projection)",
-              "as ffn_gemm2_kernel; the phase-1 average here must agree with `roofline.avg_launch_us` of the same build's bench line (HIP events",
-              "inside the library; the profiler's own overhead and the box-to-box spread of about 5 % are the difference).",
-              "Phase 1: 4*d*f*M = %.4g flop per launch / %.1f us = %.0f TFLOP/s = %.3f of the 2.5 PFLOP/s bf16 MFMA peak."
-              % (f1, avg.get("ffn_gemm1_kernel", float("nan")), f1 / avg.get("ffn_gemm1_kernel", float("nan")) / 1e6,
-                 f1 / avg.get("ffn_gemm1_kernel", float("nan")) / 1e6 / MFMA_BF16_PEAK_TFLOPS),
-              "Phase 2: 2*d*f*M = %.4g flop per launch / %.1f us = %.0f TFLOP/s = %.3f of the peak."
-              % (f2, avg.get("ffn_gemm2_kernel", float("nan")), f2 / avg.get("ffn_gemm2_kernel", float("nan")) / 1e6,
-                 f2 / avg.get("ffn_gemm2_kernel", float("nan")) / 1e6 / MFMA_BF16_PEAK_TFLOPS), ""]
-    path = os.path.join(ROOT, "profiles", "ffn_%s_kernel_stats.md" % workload)
+    lines += ["", "bench.py reports ffn_fused_kernel (both FFN phases in one launch), or the phase-1 kernel (gate / up projections + SwiGLU) as",
+              "ffn_gemm1_kernel and the phase-2 kernel (down projection) as ffn_gemm2_kernel; the average of the kernel the bench line names in",
+              "`roofline.kernel` must agree with its `roofline.avg_launch_us` (HIP events inside the library; the profiler's own overhead and the",
+              "box-to-box spread of about 5 % are the difference)."]
+    for k in FFN_KERNELS:
+        if k in avg:
+            lines.append("- %s: %.4g flop per launch / %.1f us = %.0f TFLOP/s = %.3f of the 2.5 PFLOP/s bf16 MFMA peak"
+                         % (k, work[k]["flop"], avg[k], work[k]["flop"] / avg[k] / 1e6, work[k]["flop"] / avg[k] / 1e6 / MFMA_BF16_PEAK_TFLOPS))
+    lines.append("")
+    path = os.path.join(ROOT, "profiles", "ffn_%s%s_kernel_stats.md" % (workload, profile_suffix(args)))
     open(path, "w").write("\n".join(lines))
     print(path)
 
@@ -181,29 +211,31 @@ MFMA_COUNTERS = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CYCLES", "SQ_BUSY_CU_CYCLE
                  "SQ_INSTS_VALU_MFMA_MOPS_BF16", "GRBM_GUI_ACTIVE"]
 
 
-def summarize_mfma(workload, counter_csv):
+def summarize_mfma(args, counter_csv):
     """MFMA utilisation of the FFN kernels from one rocprofv3 --pmc run (averages over the dispatches of each kernel)."""
     import collections
     import csv
+    workload = args.workload
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     dur = collections.defaultdict(dict)
     for row in csv.DictReader(open(counter_csv)):
         key = kernel_key(row["Kernel_Name"])
-        if key in ("ffn_gemm1_kernel", "ffn_gemm2_kernel"):
+        if key in FFN_KERNELS:
             acc[key][row["Counter_Name"]].append(float(row["Counter_Value"]))
             dur[key][row["Dispatch_Id"]] = float(row["End_Timestamp"]) - float(row["Start_Timestamp"])
     cfg, M = workload_shape(workload)
     rel = os.path.relpath(os.path.abspath(counter_csv), ROOT)
-    lines = ["# MFMA utilisation counters (rocprofv3 --pmc), bench.py workload %s, the two FFN kernels" % workload, "",
+    lines = ["# MFMA utilisation counters (rocprofv3 --pmc), bench.py workload %s, the FFN matrix kernels" % workload, "",
              "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box; then the summary, no GPU needed):", "",
-             "    rocprofv3 --kernel-trace --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s --steps 10 --warmup 2 --no-extras --no-cpu-baseline"
-             % (" ".join(MFMA_COUNTERS), os.path.dirname(rel), workload),
-             "    python3 bench.py --workload %s --summarize-mfma %s" % (workload, rel), "",
+             "    rocprofv3 --kernel-trace --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s%s --steps 10 --warmup 2 --no-extras --no-cpu-baseline"
+             % (" ".join(MFMA_COUNTERS), os.path.dirname(rel), workload, bench_flags(args)),
+             "    python3 bench.py --workload %s%s --summarize-mfma %s" % (workload, bench_flags(args), rel), "",
+             "(the run also holds bench.py's pass with one launch per FFN phase: the phase kernels below come from that pass)", "",
              "Averages per dispatch, as the profiler reports them: SQ_* counters are sums over the chip (SQ_VALU_MFMA_BUSY_CYCLES over its 1024 SIMDs,",
              "SQ_BUSY_CU_CYCLES over its 256 compute units, SQ_WAVE_CYCLES / SQ_WAIT_ANY over all wavefronts), GRBM_GUI_ACTIVE is the sum of the busy",
              "shader-clock cycles of the 8 accelerator dies (so cycles per launch = GRBM_GUI_ACTIVE / 8).", ""]
     names = sorted({c for k in acc for c in acc[k]})
-    kernels = sorted(acc)
+    kernels = [k for k in FFN_KERNELS if k in acc]
     lines += ["| counter | " + " | ".join(kernels) + " |", "|---|" + "---|" * len(kernels)]
     mean = {k: {c: sum(v) / len(v) for c, v in acc[k].items()} for k in kernels}
     for c in names:
@@ -211,7 +243,7 @@ def summarize_mfma(workload, counter_csv):
     lines.append("| dispatches | " + " | ".join("%d" % len(dur[k]) for k in kernels) + " |")
     lines.append("| average duration under the profiler, us | " + " | ".join("%.1f" % (sum(dur[k].values()) / len(dur[k]) / 1e3) for k in kernels) + " |")
     lines.append("")
-    flops = {"ffn_gemm1_kernel": 4.0 * cfg.d * cfg.f * M, "ffn_gemm2_kernel": 2.0 * cfg.d * cfg.f * M}
+    flops = {k: v["flop"] for k, v in ffn_kernel_work(cfg, M).items()}
     peak_per_cycle = MFMA_BF16_PEAK_TFLOPS * 1e12 / (SHADER_CLOCK_GHZ * 1e9)
     for k in kernels:
         m = mean[k]
@@ -230,22 +262,22 @@ def summarize_mfma(workload, counter_csv):
         if "SQ_LDS_BANK_CONFLICT" in m and m.get("SQ_BUSY_CU_CYCLES", 0) > 0:
             lines.append("- LDS bank-conflict cycles: %.2f %% of the busy compute-unit cycles." % (100.0 * m["SQ_LDS_BANK_CONFLICT"] / m["SQ_BUSY_CU_CYCLES"]))
         lines.append("")
-    path = os.path.join(ROOT, "profiles", "ffn_%s_mfma_utilisation.md" % workload)
+    path = os.path.join(ROOT, "profiles", "ffn_%s%s_mfma_utilisation.md" % (workload, profile_suffix(args)))
     open(path, "w").write("\n".join(lines))
     print(path)
 
 
-def stored_traffic(workload):
+def stored_traffic(workload, kernel):
     """HBM-side bytes per launch of the dominant kernel from the committed counter summary (two rocprofv3 --pmc runs,
     scaled by a plain copy of known size); None if that summary was taken on another workload or if the kernel's
     source has changed since."""
-    path = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic.json" % workload)
+    path = os.path.join(ROOT, "profiles", "ffn_%s_hbm_traffic.json" % workload)       # (the default kernel choice)
     try:
         rec = json.load(open(path))
         for rel, digest in rec["source_sha256"].items():
             if code_digest(os.path.join(ROOT, rel)) != digest:
                 return None
-        return rec["traffic_bytes_per_launch"]
+        return rec["detail"][kernel]["total_bytes"]
     except (OSError, KeyError, ValueError):
         return None
 
@@ -327,51 +359,68 @@ class Workload:
         self.main_stream.wait_event(self.ev_bvn)
 
 
-def ffn_entry(moe, torch, wl, reps):
-    """FFN figures of one workload from HIP events around every kernel: inside the whole step (the decompositions run
-    before and beside the FFN, as in the timed region of the main workload) and with the FFN call issued back to
-    back (the chip then never idles between two calls and settles at a lower clock under its power limit)."""
+def kernel_times(moe, torch, fn, reps):
+    """Average duration per kernel name (us) over `reps` calls of fn, from HIP events around every kernel, and the wall
+    time per call (s)."""
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    moe.moe_kernel_timing_select(None)
+    moe.moe_kernel_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    moe.moe_kernel_timing_enable(False)
+    kt = moe.moe_kernel_timing_read()
+    return {k: v[0] * 1e3 / v[1] for k, v in kt.items()}, dt
+
+
+def ffn_kernel_us(times):
+    """(matrix kernels, the other FFN kernels) of one call, us."""
+    gemm = sum(v for k, v in times.items() if k in ("ffn_fused_kernel", "ffn_gemm1_kernel", "ffn_gemm2_kernel"))
+    other = sum(v for k, v in times.items() if k in ("ffn_plan_kernel", "ffn_expand_fp8_kernel"))
+    return gemm, other
+
+
+def ffn_entry(moe, torch, wl, reps, kernels):
+    """FFN figures of one workload: inside the whole step (the decompositions run before and beside the FFN, as in the
+    timed region), with the FFN call issued back to back (the chip then never idles between two calls and settles at a
+    lower clock under its power limit), and with one launch per phase (moe_ffn_tile_override) for the figures per phase."""
     cfg, M = wl.cfg, wl.M
-
-    def timed(fn):
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        moe.moe_kernel_timing_select(None)
-        moe.moe_kernel_timing_enable(True)
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            fn()
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / reps
-        moe.moe_kernel_timing_enable(False)
-        kt = moe.moe_kernel_timing_read()
-        return {k: v[0] * 1e3 / v[1] for k, v in kt.items()}, dt
-
-    step_us, step_s = timed(wl.step)
-    other = sum(v for k, v in step_us.items() if k in ("ffn_plan_kernel", "ffn_expand_fp8_kernel"))
-    e = ffn_figures(cfg, M, wl.S, step_us["ffn_gemm1_kernel"], step_us["ffn_gemm2_kernel"], other)
+    step_us, step_s = kernel_times(moe, torch, wl.step, reps)
+    e = ffn_figures(cfg, M, wl.S, *ffn_kernel_us(step_us))
     e["step_kernels_us"] = step_us
     e["step_ms_with_an_event_pair_per_kernel"] = step_s * 1e3
-    b2b, _ = timed(wl.ffn)
-    e["back_to_back"] = {"phase1_us": b2b["ffn_gemm1_kernel"], "phase2_us": b2b["ffn_gemm2_kernel"],
-                         "phase1_frac_mfma_peak": 4.0 * cfg.d * cfg.f * M / b2b["ffn_gemm1_kernel"] / 1e6 / MFMA_BF16_PEAK_TFLOPS,
-                         "phase2_frac_mfma_peak": 2.0 * cfg.d * cfg.f * M / b2b["ffn_gemm2_kernel"] / 1e6 / MFMA_BF16_PEAK_TFLOPS}
+    b2b, _ = kernel_times(moe, torch, wl.ffn, reps)
+    g, _ = ffn_kernel_us(b2b)
+    e["back_to_back"] = {"matrix_kernels_us": g, "frac_mfma_peak": 6.0 * cfg.d * cfg.f * M / g / 1e6 / MFMA_BF16_PEAK_TFLOPS}
+    moe.moe_ffn_tile_override(0, 2 if kernels == 0 else kernels, 0)
+    try:
+        ph, _ = kernel_times(moe, torch, wl.step, reps)
+    finally:
+        moe.moe_ffn_tile_override(0, kernels, 0)
+    e["one_launch_per_phase"] = phase_figures(cfg, M, ph["ffn_gemm1_kernel"], ph["ffn_gemm2_kernel"])
     return e
 
 
-def ffn_figures(cfg, M, S, g1_us, g2_us, other_us):
+def phase_figures(cfg, M, g1_us, g2_us):
     f1, f2 = 4.0 * cfg.d * cfg.f * M, 2.0 * cfg.d * cfg.f * M
+    return {"phase1_us": g1_us, "phase2_us": g2_us, "phase1_tflops": f1 / g1_us / 1e6, "phase2_tflops": f2 / g2_us / 1e6,
+            "phase1_frac_mfma_peak": f1 / g1_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "phase2_frac_mfma_peak": f2 / g2_us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+            "frac_mfma_peak_both": (f1 + f2) / (g1_us + g2_us) / 1e6 / MFMA_BF16_PEAK_TFLOPS}
+
+
+def ffn_figures(cfg, M, S, gemm_us, other_us):
+    flops = 6.0 * cfg.d * cfg.f * M
     wbytes = (1 if cfg.weight_dtype == "fp8" else 2) * 3.0 * cfg.d * cfg.f * cfg.E_loc
     abytes = 4.0 * cfg.d * M + 4.0 * cfg.f * M + wbytes                 # x in, y out, h written and read, weights once
-    intensity = (f1 + f2) / abytes
+    intensity = flops / abytes
     ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
     return {"rows": M, "slices": S, "experts": cfg.E_loc, "d": cfg.d, "f": cfg.f, "weights": cfg.weight_dtype,
-            "phase1_us": g1_us, "phase2_us": g2_us, "plan_and_other_kernels_us": other_us,
-            "phase1_tflops": f1 / g1_us / 1e6, "phase2_tflops": f2 / g2_us / 1e6,
-            "phase1_frac_mfma_peak": f1 / g1_us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "phase2_frac_mfma_peak": f2 / g2_us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
-            "ffn_tflops_kernels_only": (f1 + f2) / (g1_us + g2_us) / 1e6,
-            "frac_mfma_peak_kernels_only": (f1 + f2) / (g1_us + g2_us) / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+            "matrix_kernels_us": gemm_us, "plan_and_other_kernels_us": other_us,
+            "ffn_tflops_kernels_only": flops / gemm_us / 1e6, "frac_mfma_peak_kernels_only": flops / gemm_us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
             "algorithmic_flop_per_byte": intensity, "bound": "mfma" if intensity > ridge else "hbm",
             "note": "bf16 MFMA peak is the denominator for fp8 weights too: they are dequantised to bf16 on the way to the matrix cores"}
 
@@ -379,13 +428,13 @@ def ffn_figures(cfg, M, S, g1_us, g2_us, other_us):
 def main():
     args = parse()
     if args.summarize_counters:
-        summarize_counters(args.workload, *args.summarize_counters)
+        summarize_counters(args, *args.summarize_counters)
         return
     if args.summarize_kernel_stats:
-        summarize_kernel_stats(args.workload, args.summarize_kernel_stats)
+        summarize_kernel_stats(args, args.summarize_kernel_stats)
         return
     if args.summarize_mfma:
-        summarize_mfma(args.workload, args.summarize_mfma)
+        summarize_mfma(args, args.summarize_mfma)
         return
     if args.gpus != 1:
         print("bench.py measures one GPU only (the library has no multi-GPU path); run with --gpus 1", file=sys.stderr)
@@ -396,6 +445,7 @@ def main():
     import paper_2605_26845_amd as moe
 
     moe.load()
+    moe.moe_ffn_tile_override(0, args.ffn_kernels, 0)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = workloads.CONFIGS[args.workload]
@@ -415,7 +465,9 @@ def main():
     # ---------------------------------------------------------------- timed region
     # HIP events bracket the dominant kernel only: an event pair costs about 7 us of stream time, and with one pair per
     # kernel a step of small kernels is measured slower than it is.  The other kernels are timed in a pass of their own.
-    moe.moe_kernel_timing_select("ffn_gemm1_kernel")
+    names, _ = kernel_times(moe, torch, wl.step, 1)
+    dominant = "ffn_fused_kernel" if "ffn_fused_kernel" in names else "ffn_gemm1_kernel"
+    moe.moe_kernel_timing_select(dominant)
     moe.moe_kernel_timing_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -428,29 +480,29 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     assert int(wl.offsets[-1].item()) == M
     # ---------------------------------------------------------------- per-kernel breakdown (not part of the timed region)
-    moe.moe_kernel_timing_select(None)
-    moe.moe_kernel_timing_enable(True)
-    for _ in range(max(5, args.steps // 2)):
-        wl.step()
-    torch.cuda.synchronize()
-    moe.moe_kernel_timing_enable(False)
-    kt = moe.moe_kernel_timing_read()
-    kt["ffn_gemm1_kernel"] = kt_dominant["ffn_gemm1_kernel"]          # the figure of the timed region
+    step_us, _ = kernel_times(moe, torch, wl.step, max(5, args.steps // 2))
+    kernels = {k: {"avg_us": v} for k, v in step_us.items()}
+    kernels[dominant] = {"avg_us": kt_dominant[dominant][0] * 1e3 / kt_dominant[dominant][1], "launches": kt_dominant[dominant][1],
+                         "note": "the figure of the timed region"}
+    # one launch per phase, for the figures per phase (the default issues both phases in one launch where it applies)
+    moe.moe_ffn_tile_override(0, 2 if args.ffn_kernels == 0 else args.ffn_kernels, 0)
+    ph_us, _ = kernel_times(moe, torch, wl.step, max(5, args.steps // 2))
+    moe.moe_ffn_tile_override(0, args.ffn_kernels, 0)
 
     flops_step = 6.0 * cfg.d * cfg.f * M                         # three GEMMs, 2 flops per MAC
     value = flops_step / (ms_per_step * 1e-3) / 1e12
-    kernels = {k: {"avg_us": v[0] * 1e3 / v[1], "launches": v[1]} for k, v in kt.items()}
-    g1 = kernels["ffn_gemm1_kernel"]["avg_us"]
-    g2 = kernels["ffn_gemm2_kernel"]["avg_us"]
-    flops_g1 = 4.0 * cfg.d * cfg.f * M                           # gate and up projections
-    achieved = flops_g1 / (g1 * 1e-6) / 1e12
-    roofline = {"kernel": "ffn_gemm1_kernel", "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": stored_traffic(args.workload),
-                "avg_launch_us": g1, "flop_per_launch": flops_g1}
+    dom_us = kernels[dominant]["avg_us"]
+    flops_dom = flops_step if dominant == "ffn_fused_kernel" else 4.0 * cfg.d * cfg.f * M
+    achieved = flops_dom / (dom_us * 1e-6) / 1e12
+    roofline = {"kernel": dominant, "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": stored_traffic(args.workload, dominant),
+                "avg_launch_us": dom_us, "flop_per_launch": flops_dom,
+                "what": "both FFN phases in one launch: 6*d*f*M flop" if dominant == "ffn_fused_kernel" else "phase 1 (gate / up + SwiGLU): 4*d*f*M flop"}
     n_match = int(wl.g_out["counts"][0].item())
     n_bvn = int(wl.b_out["counts"][0].item())
     decomp_us = kernels["greedy_kernel"]["avg_us"]
     bvn_us = kernels["bvn_kernel"]["avg_us"]
+    gemm_us, other_us = ffn_kernel_us({k: v["avg_us"] for k, v in kernels.items()})
     result = {
         "metric": "sliced expert-FFN TFLOP/s (% MFMA peak) + decompositions/sec at NxN",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -458,9 +510,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.describe(), "seed": cfg.seed},
         "pct_mfma_peak_whole_step": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
-        "ffn_tflops_kernels_only": flops_step / ((g1 + g2) * 1e-6) / 1e12,
-        "ffn_phase2": {"kernel": "ffn_gemm2_kernel", "avg_launch_us": g2, "achieved": 2.0 * cfg.d * cfg.f * M / g2 / 1e6,
-                       "frac": 2.0 * cfg.d * cfg.f * M / g2 / 1e6 / MFMA_BF16_PEAK_TFLOPS},
+        "ffn_tflops_kernels_only": flops_step / (gemm_us * 1e-6) / 1e12,
+        "ffn_one_launch_per_phase": phase_figures(cfg, M, ph_us["ffn_gemm1_kernel"], ph_us["ffn_gemm2_kernel"]),
         "decompositions_per_s": {"greedy_%dx%d_k%d" % (N, N, kmax): 1e6 / decomp_us, "bvn_%dx%d_full" % (N, N): 1e6 / bvn_us,
                                  "greedy_matchings": n_match, "bvn_matchings": n_bvn},
         "kernels": kernels,
@@ -470,8 +521,8 @@ def main():
     # ---------------------------------------------------------------- extras outside the timed step
     if not args.no_extras:
         ex = result["extras"] = {}
-        other = sum(v["avg_us"] for k, v in kernels.items() if k in ("ffn_plan_kernel", "ffn_expand_fp8_kernel"))
-        ex["ffn_by_config"] = {cfg.name: ffn_figures(cfg, M, wl.S, g1, g2, other)}
+        ex["ffn_by_config"] = {cfg.name: ffn_figures(cfg, M, wl.S, gemm_us, other_us)}
+        ex["ffn_by_config"][cfg.name]["one_launch_per_phase"] = result["ffn_one_launch_per_phase"]
         ex["vendor_gemm_same_shape"] = vendor_gemm(torch, wl)
         ex.update(ffn_granularity(moe, torch, np, wl))
         ex["makespan_model_us"] = makespan_extras(moe, np, cfg, wl.traffic, wl.g_out, wl.b_out, ex["expert_time_us_vs_rows"])
@@ -487,7 +538,7 @@ def main():
             if name == cfg.name:
                 continue
             other_wl = Workload(moe, torch, np, workloads, workloads.CONFIGS[name], dev, device_weights=(name == "c4"))
-            ex["ffn_by_config"][name] = ffn_entry(moe, torch, other_wl, reps=10 if name == "c2" else 3)
+            ex["ffn_by_config"][name] = ffn_entry(moe, torch, other_wl, 10 if name == "c2" else 3, args.ffn_kernels)
             ex["ffn_by_config"][name]["workload"] = other_wl.describe()
             del other_wl
             torch.cuda.empty_cache()

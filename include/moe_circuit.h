@@ -273,7 +273,9 @@ moe_status moe_combine_topk_sum(const void* y, const int32_t* row_of, const floa
  * output tiles are walked from the shape of the schedule; this call pins any of these choices for all following moe_expert_ffn_sliced(_mapped) calls of
  * the process, so that every kernel can be driven on small inputs and timed on any input.
  *   tile_rows    0 = chosen per call (the default), else 64, 128 or 256
- *   fixed_shape  0 = chosen per call (the default), 1 = always the fixed-shape kernels
+ *   kernels      0 = chosen per call (the default), 1 = always the fixed-shape kernels, 2 = the
+ *                adaptive-shape kernels with one launch per phase instead of both phases in one
+ *                launch (where the adaptive-shape kernels apply)
  *   panel_groups 0 = chosen per call (the default), else the number of column groups (of up to 8
  *                column tiles) the tile walk finishes for all rows before it moves on to the next
  *                columns (a large value = all columns in one sweep per row group)
@@ -281,7 +283,7 @@ moe_status moe_combine_topk_sum(const void* y, const int32_t* row_of, const floa
  * choice agree within the rounding of the fp32 sums (the order of the additions differs).
  * Returns MOE_ERR_INVALID_ARG for other values (nothing changes then).
  * ------------------------------------------------------------------------------------------- */
-moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape, int panel_groups);
+moe_status moe_ffn_tile_override(int tile_rows, int kernels, int panel_groups);
 
 /* ---------------------------------------------------------------------------------------------
  * moe_makespan_model -- Section 5 (Setup: "Execution time"), host-side.  Analytic completion time

@@ -386,11 +386,11 @@ def moe_combine_topk_sum(y, row_of, gate=None, out=None):
     return out
 
 
-def moe_ffn_tile_override(tile_rows: int = 0, fixed_shape: bool = False, panel_groups: int = 0):
-    """Test / measurement hook: pin the row-block height (64, 128, 256; 0 = automatic), the fixed-shape kernels and / or
-    the panel width of the tile walk for the following FFN calls of this process.  Call with no arguments to restore
-    the defaults."""
-    _check(load().moe_ffn_tile_override(int(tile_rows), 1 if fixed_shape else 0, int(panel_groups)), "moe_ffn_tile_override")
+def moe_ffn_tile_override(tile_rows: int = 0, kernels: int = 0, panel_groups: int = 0):
+    """Test / measurement hook: pin the row-block height (64, 128, 256; 0 = automatic), the kernel family (1 = fixed
+    shape, 2 = adaptive shape with one launch per phase) and / or the panel width of the tile walk for the following
+    FFN calls of this process.  Call with no arguments to restore the defaults."""
+    _check(load().moe_ffn_tile_override(int(tile_rows), int(kernels), int(panel_groups)), "moe_ffn_tile_override")
 
 
 def moe_kernel_timing_enable(on: bool):

@@ -40,6 +40,7 @@ struct FfnArgs {
     const int32_t* row_map;            // [M] or null: row m of the schedule is row row_map[m] of x and of y
     const float* row_gate;             // [M] or null: y row is scaled by row_gate[m]
     int panel1, panel2;                // column groups per panel of the tile walk, phase 1 / phase 2 (see TileGeom)
+    int* ready;                        // [row blocks] column units of h complete per row block (fused launch), zeroed by the plan kernel
 };
 // row of x that schedule row m reads (phase 1) / row of y it writes (phase 2)
 __device__ __forceinline__ int mapped_row(const FfnArgs& a, int m) { return a.row_map ? a.row_map[m] : m; }
@@ -97,7 +98,8 @@ __device__ __forceinline__ void plan_scan2(int a, int b, int tid, int* wave_a, i
     excl_b = base_b + ib - b;
 }
 __global__ __launch_bounds__(PLAN_THREADS)
-void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int M, int bm, int cap, int4* __restrict__ plan) {
+void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int M, int bm, int cap, int4* __restrict__ plan,
+                     int* __restrict__ ready) {
     __shared__ int wave_tot[PLAN_THREADS / 64], wave_tot2[PLAN_THREADS / 64];
     const int tid = threadIdx.x;
     auto bounds = [&](int g, int& lo, int& hi) {
@@ -140,6 +142,7 @@ void ffn_plan_kernel(const int32_t* __restrict__ offsets, int G, int e_loc, int 
             plan[PLAN_HDR + at_partial] = make_int4(row, hi, g % e_loc, hi - row > 128 ? 0 : 1);
         }
     }
+    for (int i = tid; i < min(run_full, cap); i += PLAN_THREADS) ready[i] = 0;      // per row block: column units of h complete
     if (tid == 0) plan[0] = make_int4(min(run_full, cap), 0, 0, 0);
     if (tid >= 1 && tid < PLAN_HDR) plan[tid] = make_int4(0, 0, 0, 0);      // tile queue counters
 }
@@ -568,11 +571,18 @@ constexpr int ADAPTIVE_LDS = STAGE_OFF + 8 * STAGE_WAVE;      // 160 KiB: all of
 // GATHER (phase 1 with a row map): the rows of a tile lie anywhere in x, so every thread carries the 64-bit address of
 // its rows; otherwise the rows of a tile are consecutive and one buffer descriptor per tile (64-bit base at the
 // tile's first row) plus 32-bit offsets inside the tile address them, whatever the size of the operand.
-template <int PHASE, bool GATHER>
-__global__ __launch_bounds__(512, 1)
-void ffn_adaptive_kernel(FfnArgs a) {
+// FUSED (both phases in one launch, see ffn_fused_kernel): a phase-1 tile, once its rows of h are stored, adds the
+// column units it covered to the ready counter of its row block; a phase-2 ticket is handed to the workgroup only when
+// the counter of its row block has reached the number of column units of h.  The hidden activations cross from one
+// workgroup to another inside the launch, possibly from one die's L2 to another's: their stores (phase 1) and their
+// loads (phase 2) are issued at device scope (the sc1 bit of the instruction: the store is written through to where
+// every die sees it before it counts as complete, the load does not take a copy that is private to its die), and the
+// counters are device-scope atomics; a writer signals after all its stores have completed (vmcnt(0) in every wavefront,
+// then a barrier), a reader issues its loads after it has seen the count.
+constexpr int DEVICE_SCOPE = 16;       // cache-policy bit sc1 of a buffer instruction
+template <int PHASE, bool GATHER, bool FUSED>
+__device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned char* smem) {
     static_assert(PHASE == 1 || !GATHER, "only phase 1 gathers its rows");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // next tile: (block, tile index, class, first row, end row, expert); block -1 = none.  It shares its bytes with
     // wavefront 0's output staging: written by that wavefront after its read-out, read by the others before the
     // next read-out begins (inside the slab loop, or ahead of a barrier).
@@ -626,12 +636,40 @@ void ffn_adaptive_kernel(FfnArgs a) {
             if (st < 0) { if (++tries == 8) break; q = (q + 1) & 7; }
             st = look(atomicAdd(&queues[q], 1));
         }
+        if (FUSED && PHASE == 2 && blk >= 0) {
+            // The rows of h this tile reads are complete when every phase-1 tile of the row block has signalled.  Phase-1
+            // tickets are all taken before the first phase-2 ticket, and a workgroup that holds a phase-1 ticket never
+            // waits, so the wait ends; the bound on it only turns a defect into a flagged wrong result instead of a hang.
+            const int need = a.f / 128;
+            for (int spins = 0; __hip_atomic_load(&a.ready[blk], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need; ++spins) {
+                __builtin_amdgcn_s_sleep(32);                                           // about 2048 cycles
+                if (spins > (1 << 20)) { atomicOr((int*)&a.plan[0].y, 1); break; }      // seconds: a defect, flagged in the plan header
+            }
+        }
         s_ticket[0] = blk; s_ticket[1] = blk >= 0 ? (unit >> cls) : 0; s_ticket[2] = cls;
         s_ticket[3] = info.x; s_ticket[4] = info.y; s_ticket[5] = info.z;      // the plan entry travels with the ticket
     };
     if (tid == 0) fetch(atomicAdd(&queues[my_xcd], 1));
     __syncthreads();
     if (s_ticket[0] < 0) return;
+
+    // FUSED phase 1: the last two tiles of this workgroup whose completion has not been signalled yet (row block and
+    // column units; block -1 = none).  A tile's output stores are the youngest memory operations when the next tile
+    // begins, so waiting for them there would also wait for that tile's second slab; one tile later they are older
+    // than everything the opening wait of a tile leaves outstanding (its second slab and the stores of the tile before
+    // it) and are known to be complete at no extra cost.  So tile t is signalled when tile t + 2 opens, and what is left
+    // when the workgroup runs out of tiles is signalled after a full wait.
+    int sig_blk[2] = {-1, -1}, sig_units[2] = {0, 0};                // [0] = the tile before the previous one
+    auto signal_ready = [&](int n) __attribute__((always_inline)) {
+        // (every wavefront has passed the wait that covers these stores, and a barrier since)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (i < n && tid == 0 && sig_blk[i] >= 0)
+                __hip_atomic_fetch_add(&a.ready[sig_blk[i]], sig_units[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (n == 1) { sig_blk[0] = sig_blk[1]; sig_units[0] = sig_units[1]; sig_blk[1] = -1; }
+        else        { sig_blk[0] = sig_blk[1] = -1; }
+    };
+    int cur_blk = 0;
 
     // ---- per-tile copy state: buffer resources and scalar offsets carry what is uniform, the per-thread byte offsets
     //      are fixed for a tile, so a copy costs no vector ALU work.  Rows past the end of the block re-read its last row.
@@ -651,6 +689,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
     auto setup = [&](auto tag, int nt_) __attribute__((always_inline)) {
         typedef Cls<decltype(tag)::value> C;
         nt = __builtin_amdgcn_readfirstlane(nt_);
+        if (FUSED && PHASE == 1) cur_blk = __builtin_amdgcn_readfirstlane(s_ticket[0]);
         m0 = __builtin_amdgcn_readfirstlane(s_ticket[3]); m_end = __builtin_amdgcn_readfirstlane(s_ticket[4]);
         const int e = __builtin_amdgcn_readfirstlane(s_ticket[5]);
         const int rows = min(C::BMc, m_end - m0);
@@ -696,7 +735,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
             } else {
                 const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)aB, 0, 0xFFFFFFFF, 0x00020000);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
-                                                         a_voff[n], koff, 0, 0);
+                                                         a_voff[n], koff, 0, FUSED && PHASE == 2 ? DEVICE_SCOPE : 0);
             }
         } else {
             const int j = n - C::CA;
@@ -759,6 +798,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][q][v] = 0.f;
         const int em0 = m0, em_end = m_end, ent = nt;                   // this tile's rows and column unit, for the read-out
+        const int eblk = cur_blk;
         int nblk = -1, nnt = 0, ncls = 0;                                // ticket of the next tile
         bool chained = false;                                            // the next tile's slab 0 was issued inside this tile
 
@@ -766,6 +806,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
         // stores need not be awaited when their number is known (memory operations of a wavefront are counted in order).
         if (counted_stores) wait_vmcnt<(NSS - 1) * LPS + NSTORE>(); else wait_vmcnt<(NSS - 1) * LPS>();
         lds_barrier();                   // slab 0 is in LDS
+        if (FUSED && PHASE == 1) signal_ready(1);
         // Ticket of the next tile: the counter's old value returns while slab 0 is multiplied and is turned into a
         // ticket after that slab (waiting for it here would hold wavefront 0, and with it every barrier, until the
         // copies just issued have landed: memory operations of a wavefront return in order).
@@ -935,7 +976,8 @@ void ffn_adaptive_kernel(FfnArgs a) {
                     if (!scatter) {
 #pragma unroll
                         for (int i = 0; i < 32 / RPI; ++i)
-                            __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO, (mb * 32 + i * RPI + sr) * rowb + hq * SROW + sc * 16, 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO, (mb * 32 + i * RPI + sr) * rowb + hq * SROW + sc * 16, 0,
+                                                                   FUSED && PHASE == 1 ? DEVICE_SCOPE : 0);
                     } else {
 #pragma unroll
                         for (int i = 0; i < 32 / RPI; ++i) {
@@ -948,6 +990,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
                 __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
             }
         }
+        if (FUSED && PHASE == 1) { sig_blk[1] = eblk; sig_units[1] = min(C::U, NU - ent * C::U); }
         return nblk >= 0 ? ncls : -1;
     };
 
@@ -957,6 +1000,31 @@ void ffn_adaptive_kernel(FfnArgs a) {
         if (cls == 0)      cls = run_tile(std::integral_constant<int, 0>{});
         else               cls = run_tile(std::integral_constant<int, 1>{});
     }
+    if (FUSED && PHASE == 1) {           // the last two tiles of this workgroup
+        wait_vmcnt<0>();
+        lds_barrier();
+        signal_ready(2);
+    }
+}
+
+template <int PHASE, bool GATHER>
+__global__ __launch_bounds__(512, 1)
+void ffn_adaptive_kernel(FfnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    ffn_adaptive_body<PHASE, GATHER, false>(a, smem);
+}
+
+// Both phases in one launch: a workgroup works through the phase-1 tiles until none is left to hand out, then
+// through the phase-2 tiles, each of which starts when the rows of h it reads are complete (release by the writers,
+// acquire by the reader, at device scope).  The tail of phase 1 is filled with phase-2 tiles, and a call costs one
+// launch of the matrix kernels whatever the number of slices.
+template <bool GATHER>
+__global__ __launch_bounds__(512, 1)
+void ffn_fused_kernel(FfnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    ffn_adaptive_body<1, GATHER, true>(a, smem);
+    __syncthreads();                     // the ticket area and the staging buffers change hands
+    ffn_adaptive_body<2, false, true>(a, smem);
 }
 
 // Expands block-scaled E4M3 codes [rows][cols] to bf16, eight values per thread and step (HBM bound: 3 bytes per weight).
@@ -976,9 +1044,10 @@ void ffn_expand_fp8_kernel(const unsigned char* __restrict__ codes, const float*
 
 int plan_capacity(int M) { return M / 64 + MAX_GROUPS + 1; }
 size_t h_bytes(int M, int f) { return (((size_t)M * f * 2) + 255) & ~(size_t)255; }
+size_t ready_bytes(int M) { return (((size_t)plan_capacity(M) * sizeof(int)) + 255) & ~(size_t)255; }
 
 std::atomic<int> g_force_rows{0};          // moe_ffn_tile_override: 0 = rows per tile chosen per call, else 64 / 128 / 256
-std::atomic<int> g_force_fixed{0};         //                        1 = never the adaptive-shape kernels
+std::atomic<int> g_force_kernels{0};       //                        1 = never the adaptive-shape kernels, 2 = adaptive-shape kernels, one launch per phase
 std::atomic<int> g_force_panel{0};         //                        0 = panel width of the tile walk chosen per call, else column groups per panel
 std::atomic<int> g_num_cus[64];            // compute units of device d (0 = not asked yet)
 int num_cus() {
@@ -1050,7 +1119,28 @@ moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s)
     return k.done();
 }
 
+template <bool GATHER>
+moe_status launch_fused(const FfnArgs& a, long long max_tiles, hipStream_t s) {
+    static moe::DeviceOnce attr;
+    auto kern = ffn_fused_kernel<GATHER>;
+    int dev;
+    if (attr.needed(dev)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ADAPTIVE_LDS);
+        if (e != hipSuccess) { moe::note_hip_error(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)"); return MOE_ERR_HIP; }
+        attr.mark(dev);
+    }
+    const long long slots = num_cus();
+    const int grid = (int)(max_tiles < slots ? max_tiles : slots);
+    moe::LaunchScope k("ffn_fused_kernel", s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ADAPTIVE_LDS, s, a);
+    return k.done();
+}
+
 moe_status launch_both_adaptive(const FfnArgs& a, long long max_blocks, hipStream_t s) {
+    if (g_force_kernels.load(std::memory_order_relaxed) != 2) {
+        const long long tiles = max_blocks * std::max(a.f / 128, a.d / 256);
+        return a.row_map ? launch_fused<true>(a, tiles, s) : launch_fused<false>(a, tiles, s);
+    }
     moe_status st = a.row_map ? launch_adaptive<1, true>(a, max_blocks * (a.f / 128), s)
                               : launch_adaptive<1, false>(a, max_blocks * (a.f / 128), s);
     if (st != MOE_OK) return st;
@@ -1068,15 +1158,15 @@ moe_status launch_both(const FfnArgs& a, long long max_blocks, hipStream_t s) {
 
 extern "C" size_t moe_ffn_workspace_bytes(int M, int d, int f) {
     if (M < 0 || d < 1 || f < 1) return 0;
-    return h_bytes(M, f) + (size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4);
+    return h_bytes(M, f) + (size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4) + ready_bytes(M);
 }
 
-extern "C" moe_status moe_ffn_tile_override(int tile_rows, int fixed_shape, int panel_groups) {
+extern "C" moe_status moe_ffn_tile_override(int tile_rows, int kernels, int panel_groups) {
     if (tile_rows != 0 && tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return MOE_ERR_INVALID_ARG;
-    if (fixed_shape != 0 && fixed_shape != 1) return MOE_ERR_INVALID_ARG;
+    if (kernels < 0 || kernels > 2) return MOE_ERR_INVALID_ARG;
     if (panel_groups < 0) return MOE_ERR_INVALID_ARG;
     g_force_rows.store(tile_rows, std::memory_order_relaxed);
-    g_force_fixed.store(fixed_shape, std::memory_order_relaxed);
+    g_force_kernels.store(kernels, std::memory_order_relaxed);
     g_force_panel.store(panel_groups, std::memory_order_relaxed);
     return MOE_OK;
 }
@@ -1144,6 +1234,7 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     a.sg = s_gate; a.su = s_up; a.sd = s_down;
     int4* plan = (int4*)((char*)workspace + h_bytes(M, f));
     a.plan = plan;
+    a.ready = (int*)(plan + PLAN_HDR + plan_capacity(M));
     a.d = d; a.f = f;
     a.row_map = row_map; a.row_gate = row_gate;
     a.panel1 = panel_width(f / 128, (size_t)2 * d * f * 2, (size_t)256 * d * 2);
@@ -1152,13 +1243,13 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     {
         moe::LaunchScope k("ffn_plan_kernel", s);
         hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, (int)G, E_loc, M, bm,
-                           plan_capacity(M), plan);
+                           plan_capacity(M), plan, a.ready);
         moe_status st = k.done();
         if (st != MOE_OK) return st;
     }
     const long long max_blocks = M / bm + G;
     // (the adaptive kernel chains tiles over their last two slabs: at least four 64-wide slabs, f >= 256; d always is)
-    if (bm == 256 && !fp8 && f >= 256 && !g_force_fixed.load(std::memory_order_relaxed)) return launch_both_adaptive(a, max_blocks, s);
+    if (bm == 256 && !fp8 && f >= 256 && g_force_kernels.load(std::memory_order_relaxed) != 1) return launch_both_adaptive(a, max_blocks, s);
     if (fp8) {
         if (bm == 256) return launch_both<256, true>(a, max_blocks, s);
         if (bm == 128) return launch_both<128, true>(a, max_blocks, s);

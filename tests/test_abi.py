@@ -40,7 +40,7 @@ def test_host_side_argument_checks_need_no_gpu():
     # both pins of the residual width at once
     assert L.moe_decompose_greedy(ctypes.c_void_p(8), 1, 4, 1, 2 | 4, None, None, ctypes.c_void_p(8), None, None, None) == -1
     assert L.moe_decompose_profile(None, 3) == -1 and L.moe_decompose_profile(None, 0) == 0
-    assert L.moe_ffn_tile_override(100, 0, 0) == -1 and L.moe_ffn_tile_override(0, 2, 0) == -1
+    assert L.moe_ffn_tile_override(100, 0, 0) == -1 and L.moe_ffn_tile_override(0, 3, 0) == -1
     assert L.moe_ffn_tile_override(0, 0, -1) == -1 and L.moe_ffn_tile_override(0, 0, 0) == 0
     # a schedule too long for the built-in work area of the allocation-free slice table
     assert L.moe_slice_table_static(ctypes.c_void_p(8), 8, 4, 1, 8, 0, ctypes.c_void_p(8), ctypes.c_void_p(8), ctypes.c_void_p(8),

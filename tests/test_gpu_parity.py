@@ -507,11 +507,13 @@ def multi_tile_case(dtype):
     return _MULTI[dtype]
 
 
-@pytest.mark.parametrize("dtype,tile_rows,fixed", [("bf16", 0, False), ("bf16", 256, True), ("bf16", 128, False), ("bf16", 64, False),
-                                                   ("fp8", 256, False), ("fp8", 128, False), ("fp8", 64, False)])
+@pytest.mark.parametrize("dtype,tile_rows,fixed", [("bf16", 0, 0), ("bf16", 0, 2), ("bf16", 256, 1), ("bf16", 128, 0), ("bf16", 64, 0),
+                                                   ("fp8", 256, 0), ("fp8", 128, 0), ("fp8", 64, 0)])
 def test_ffn_many_tiles_per_workgroup_all_rows(lib, dtype, tile_rows, fixed):
     """Every row against the oracle on a schedule large enough that the tile loop, the hand-over from one tile to the
-    next (chained or not), ticket stealing and the counted-store wait all run, for every kernel family."""
+    next (chained or not), ticket stealing, the counted-store wait and (both phases in one launch, the default for bf16
+    weights and 256-row tiles) the wait of a phase-2 tile for its rows of h all run, for every kernel family
+    (`fixed`: 0 = the call's own choice, 1 = fixed-shape kernels, 2 = adaptive-shape kernels, one launch per phase)."""
     say("ffn many tiles per workgroup", dtype, tile_rows, fixed)
     c = multi_tile_case(dtype)
     w = upload_weights(c["W"])
