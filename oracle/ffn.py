@@ -1,6 +1,6 @@
 """Expert FFN oracle -- TEST INFRASTRUCTURE ONLY (numpy, float64).
 
-Section 2.1 of the paper ("Compute: each expert processes its assigned tokens") leaves the
+Section 2.1 of the paper (the compute step between dispatch and combine) leaves the
 expert function open; the workloads here use the gated SwiGLU feed-forward of the models the
 paper traces (Mixtral, DeepSeek-MoE):
 
