@@ -41,6 +41,23 @@ struct FfnArgs {
     const float* row_gate;             // [M] or null: y row is scaled by row_gate[m]
     int panel1, panel2;                // column groups per panel of the tile walk, phase 1 / phase 2 (see TileGeom)
     int* ready;                        // [row blocks] column units of h complete per row block (fused launch), zeroed by the plan kernel
+    // The plain grouped GEMM of the adaptive-shape kernels' "phase 2": out[m][n] = sum_k A[m][k] * B_e[n][k] for the
+    // rows m of every row block (expert e), n over NU units of 256 columns.  The forward pass sets A = h, B = w_down,
+    // out = y; the backward pass runs it on other operands (see moe_expert_ffn_backward_sliced).
+    struct Gemm {
+        const __bf16* A; int lda;          // [rows][lda], K contiguous
+        const __bf16* B; int ldb;          // B_e = B + e * strideB: [NU * 256][ldb], K contiguous
+        long long strideB;
+        __bf16* O; int ldo;
+        int K, NU;
+        const int4* etab;                  // or null.  Per expert (k0, K, r0, 0): the tile contracts over columns k0 .. k0 + K - 1 of
+                                           // A and B, and row m of the schedule is row m - r0 of A
+        int* queues;                       // 8 tile queue counters, zero at launch
+    } g2;
+    // backward pass, phase 1 with the gradient read-out (EPI == 1): dh in, [dg | du] and h out
+    const __bf16* dh; int lddh;            // [M][lddh]
+    __bf16* dgu;                           // [M][2 f]: dg in columns 0 .. f-1, du in f .. 2f-1
+    int* queues1;                          // 8 tile queue counters of phase 1, zero at launch
 };
 // row of x that schedule row m reads (phase 1) / row of y it writes (phase 2)
 __device__ __forceinline__ int mapped_row(const FfnArgs& a, int m) { return a.row_map ? a.row_map[m] : m; }
@@ -580,9 +597,12 @@ constexpr int ADAPTIVE_LDS = STAGE_OFF + 8 * STAGE_WAVE;      // 160 KiB: all of
 // counters are device-scope atomics; a writer signals after all its stores have completed (vmcnt(0) in every wavefront,
 // then a barrier), a reader issues its loads after it has seen the count.
 constexpr int DEVICE_SCOPE = 16;       // cache-policy bit sc1 of a buffer instruction
-template <int PHASE, bool GATHER, bool FUSED>
+// EPI (phase 1): 0 = h = silu(g) * u is stored; 1 = the backward pass: with dh read from memory, dg = dh * u * silu'(g) and
+// du = dh * silu(g) are stored side by side and h beside them.
+template <int PHASE, bool GATHER, bool FUSED, int EPI = 0>
 __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned char* smem) {
     static_assert(PHASE == 1 || !GATHER, "only phase 1 gathers its rows");
+    static_assert(EPI == 0 || (PHASE == 1 && !FUSED), "the gradient read-out belongs to phase 1 of a launch of its own");
     // next tile: (block, tile index, class, first row, end row, expert); block -1 = none.  It shares its bytes with
     // wavefront 0's output staging: written by that wavefront after its read-out, read by the others before the
     // next read-out begins (inside the slab loop, or ahead of a barrier).
@@ -591,11 +611,12 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, lhi = lane >> 5;
-    const int K = PHASE == 1 ? a.d : a.f;
-    const int NU = PHASE == 1 ? a.f / 128 : a.d / 256;          // column units
+    int K = PHASE == 1 ? a.d : a.g2.K;                          // (per tile when the GEMM has an expert table)
+    const int NU = PHASE == 1 ? a.f / 128 : a.g2.NU;            // column units
+    const int lda = PHASE == 1 ? a.d : a.g2.lda, ldb = PHASE == 1 ? a.d : a.g2.ldb;      // row pitch of the operands, elements
     TileGeom geom;
     geom.init(a.plan[0].x, NU, PHASE == 1 ? a.panel1 : a.panel2);
-    int* queues = (int*)(a.plan + (PHASE == 1 ? 1 : 3));
+    int* queues = PHASE == 1 ? a.queues1 : a.g2.queues;
     const int my_xcd = blockIdx.x & 7;
 
     // Slab layout: row-major, 16-byte chunk c of row r sits at position c ^ swz(r); swz(r) = (r >> 2) & 3 for 64-byte
@@ -673,7 +694,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
 
     // ---- per-tile copy state: buffer resources and scalar offsets carry what is uniform, the per-thread byte offsets
     //      are fixed for a tile, so a copy costs no vector ALU work.  Rows past the end of the block re-read its last row.
-    const __bf16* Abase = (PHASE == 1 ? a.x : (const __bf16*)a.h);
+    const __bf16* Abase = (PHASE == 1 ? a.x : a.g2.A);
     unsigned long long aB = 0;                         // address of the tile's first row of the A operand (plain rows)
     const unsigned char* a_ptr[GATHER ? 4 : 1];        // address of this thread's chunk of each of its rows (gathered rows)
     // B rows come from w_gate / w_up (phase 1) or w_down (phase 2) of the tile's expert: base address of the first and
@@ -694,32 +715,39 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
         const int e = __builtin_amdgcn_readfirstlane(s_ticket[5]);
         const int rows = min(C::BMc, m_end - m0);
         const int row0 = C::ROWB == 128 ? row0_128 : row0_64, kcg = C::ROWB == 128 ? kcg_128 : kcg_64;
+        int k0 = 0, r0 = 0;                                               // columns and rows of the operands the tile starts at
+        if (PHASE == 2 && a.g2.etab) {
+            const __attribute__((address_space(4))) int* t = (const __attribute__((address_space(4))) int*)a.g2.etab + 4 * e;
+            k0 = t[0]; K = t[1]; r0 = t[2];
+        }
         if constexpr (GATHER) {
 #pragma unroll
             for (int i = 0; i < C::CA; ++i) {
                 const int m = m0 + min(row0 + C::RPC * i, rows - 1);
-                a_ptr[i] = (const unsigned char*)Abase + ((unsigned long long)(unsigned int)a.row_map[m] * (unsigned int)K + kcg * 8) * 2ull;
+                a_ptr[i] = (const unsigned char*)Abase + ((unsigned long long)(unsigned int)a.row_map[m] * (unsigned int)lda + kcg * 8) * 2ull;
             }
         } else {
-            aB = (unsigned long long)Abase + (unsigned long long)(unsigned int)m0 * (unsigned int)K * 2ull;
+            aB = (unsigned long long)Abase + ((unsigned long long)(unsigned int)(m0 - r0) * (unsigned int)lda + (unsigned int)k0) * 2ull;
 #pragma unroll
-            for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)(min(row0 + C::RPC * i, rows - 1) * K + kcg * 8) * 2u;
+            for (int i = 0; i < C::CA; ++i) a_voff[i] = (unsigned int)(min(row0 + C::RPC * i, rows - 1) * lda + kcg * 8) * 2u;
         }
+        // the B rows of the tile: 64-bit base at the tile's first column unit, 32-bit offsets from there
+        const int u0 = min(nt * C::U, NU - 1);
         if (PHASE == 1) {
-            wB = (unsigned long long)((const __bf16*)a.wg + (size_t)e * a.f * K);
-            wB_up = (unsigned long long)((const __bf16*)a.wu + (size_t)e * a.f * K) - wB;
+            wB = (unsigned long long)((const __bf16*)a.wg + ((size_t)e * a.f + (size_t)u0 * 128) * ldb);
+            wB_up = (unsigned long long)((const __bf16*)a.wu + ((size_t)e * a.f + (size_t)u0 * 128) * ldb) - wB;
         } else {
-            wB = (unsigned long long)((const __bf16*)a.wd + (size_t)e * a.d * K);
+            wB = (unsigned long long)(a.g2.B + (size_t)e * a.g2.strideB + (size_t)u0 * 256 * ldb + k0);
             wB_up = 0;
         }
-        b_voff = (unsigned int)(row0 * K + kcg * 8) * 2u;
+        b_voff = (unsigned int)(row0 * ldb + kcg * 8) * 2u;
         constexpr int CPSTRIP = 128 / C::RPC;                             // copies per 128-row strip of the B slab
 #pragma unroll
         for (int j = 0; j < C::CB; ++j) {
             const int strip = j / CPSTRIP;
-            const int ug = min(nt * C::U + (strip >> 1), NU - 1);
-            const int strip_row = PHASE == 1 ? ug * 128 : ug * 256 + (strip & 1) * 128;   // row inside the expert's matrix
-            b_soff[j] = (unsigned int)(strip_row + (j % CPSTRIP) * C::RPC) * (unsigned int)K * 2u;
+            const int ug = min(nt * C::U + (strip >> 1), NU - 1) - u0;
+            const int strip_row = PHASE == 1 ? ug * 128 : ug * 256 + (strip & 1) * 128;   // row from the tile's first B row
+            b_soff[j] = (unsigned int)(strip_row + (j % CPSTRIP) * C::RPC) * (unsigned int)ldb * 2u;
         }
     };
     // copy n of slab s into slab buffer sbuf
@@ -771,7 +799,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
         constexpr int MB = C::MB, NQ = C::NQ, NSS = C::NSS, SUB = C::SUB;
         constexpr int ROWB = C::ROWB, NMF = MB * NQ, NR = MB + NQ;
         constexpr int LPS = C::NCOPY;                                   // copies every wavefront issues per slab
-        constexpr int NSTORE = MB * (PHASE == 1 ? 4 : 8);               // 1 KiB stores per wavefront and tile
+        constexpr int NSTORE = MB * (PHASE == 1 ? 4 : 8) * (EPI == 1 ? 3 : 1);      // 1 KiB stores per wavefront and tile
         static_assert((NSS - 1) * C::NCOPY + NSTORE < 64 && NSS * C::SLAB <= STAGE_OFF, "pipeline shape");
         static_assert(Cls<0>::MB == Cls<1>::MB, "a tile of either class issues NSTORE output stores");
         const int NS = K / (ROWB / 2);
@@ -932,16 +960,22 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
         const bool scatter = PHASE == 2 && (a.row_map || a.row_gate);
         // plain case: rows and columns past the end fall outside the buffer descriptor and are dropped, so every
         // wavefront issues exactly NSTORE stores per tile
-        const int rowb = (PHASE == 1 ? a.f : a.d) * 2;
-        __bf16* obase = (PHASE == 1 ? a.h + (long long)wrow * a.f + ug * 128 + (wn & 1) * 64
-                                    : a.y + (long long)wrow * a.d + ug * 256 + (wn & 1) * 128);
+        constexpr int NPASS = EPI == 1 ? 3 : 1;                             // outputs per tile: h, or dg, du and h
         const int live = ug < NU ? min(max(em_end - wrow, 0), 32 * MB) : 0;
-        const unsigned long long ob = (unsigned long long)obase;          // (made uniform explicitly: the descriptor must sit in scalar registers)
-        const unsigned int ob_lo = (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)ob);       // (the builtin returns int:
-        const unsigned int ob_hi = (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)(ob >> 32)); //  widen as unsigned)
-        const unsigned long long ob_u = ((unsigned long long)ob_hi << 32) | ob_lo;
-        const __amdgpu_buffer_rsrc_t rsO =
-            __builtin_amdgcn_make_buffer_rsrc((void*)ob_u, 0, __builtin_amdgcn_readfirstlane(live * rowb), 0x00020000);
+        __amdgpu_buffer_rsrc_t rsO[NPASS];
+        int rowb[NPASS];
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            __bf16* obase;
+            if (PHASE == 2)                  { obase = a.g2.O + (long long)wrow * a.g2.ldo + ug * 256 + (wn & 1) * 128; rowb[pass] = a.g2.ldo * 2; }
+            else if (EPI == 0 || pass == 2)  { obase = a.h + (long long)wrow * a.f + ug * 128 + (wn & 1) * 64; rowb[pass] = a.f * 2; }
+            else                             { obase = a.dgu + (long long)wrow * (2 * a.f) + pass * a.f + ug * 128 + (wn & 1) * 64; rowb[pass] = a.f * 4; }
+            const unsigned long long ob = (unsigned long long)obase;      // (made uniform explicitly: the descriptor must sit in scalar registers)
+            const unsigned int ob_lo = (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)ob);       // (the builtin returns int:
+            const unsigned int ob_hi = (unsigned int)__builtin_amdgcn_readfirstlane((unsigned int)(ob >> 32)); //  widen as unsigned)
+            const unsigned long long ob_u = ((unsigned long long)ob_hi << 32) | ob_lo;
+            rsO[pass] = __builtin_amdgcn_make_buffer_rsrc((void*)ob_u, 0, __builtin_amdgcn_readfirstlane(live * rowb[pass]), 0x00020000);
+        }
         counted_stores = !scatter;
         if (!scatter || ug < NU) {
 #pragma unroll
@@ -954,6 +988,17 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
 #pragma unroll
                         for (int v = 0; v < 16; ++v) acc[mb][q][v] *= gate;
                 }
+                // backward pass: the gradient of the hidden activations at this lane's 2 x 4 groups of 4 columns (rows
+                // and units past the end read the last valid ones; what is computed from them is not stored)
+                u32x2 dhv[EPI == 1 ? 8 : 1];
+                if constexpr (EPI == 1) {
+                    const int row_c = min(wrow + mb * 32 + el31, em_end - 1);
+                    const __bf16* src = a.dh + (long long)row_c * a.lddh + min(ug, NU - 1) * 128 + (wn & 1) * 64 + elhi * 4;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) dhv[c] = *reinterpret_cast<const u32x2*>(src + c * 8);
+                }
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
 #pragma unroll
                 for (int hq = 0; hq < NH; ++hq) {
 #pragma unroll
@@ -961,10 +1006,22 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
 #pragma unroll
                         for (int vg = 0; vg < 4; ++vg) {
                             float hv[4];
+                            if constexpr (EPI == 1) {
+                                const bf16x4 d4 = __builtin_bit_cast(bf16x4, dhv[q * 4 + vg]);
 #pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                hv[j] = PHASE == 1 ? silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j]
-                                                   : acc[mb][hq * 2 + q][vg * 4 + j];
+                                for (int j = 0; j < 4; ++j) {
+                                    const float g = acc[mb][q][vg * 4 + j], u = acc[mb][q + 2][vg * 4 + j], dh = (float)d4[j];
+                                    const float sig = __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+                                    hv[j] = pass == 0 ? dh * u * (sig * (1.0f + g * (1.0f - sig)))       // dg = dh * u * silu'(g)
+                                          : pass == 1 ? dh * (g * sig)                                    // du = dh * silu(g)
+                                                      : (g * sig) * u;                                    // h
+                                }
+                            } else {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    hv[j] = PHASE == 1 ? silu(acc[mb][q][vg * 4 + j]) * acc[mb][q + 2][vg * 4 + j]
+                                                       : acc[mb][hq * 2 + q][vg * 4 + j];
+                            }
                             *reinterpret_cast<u32x2*>(wr + (((q * 4 + vg) ^ swz(el31)) << 4)) = pack4(hv[0], hv[1], hv[2], hv[3]);
                         }
                     u32x4 v[32 / RPI];
@@ -976,16 +1033,17 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
                     if (!scatter) {
 #pragma unroll
                         for (int i = 0; i < 32 / RPI; ++i)
-                            __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO, (mb * 32 + i * RPI + sr) * rowb + hq * SROW + sc * 16, 0,
+                            __builtin_amdgcn_raw_buffer_store_b128(v[i], rsO[pass], (mb * 32 + i * RPI + sr) * rowb[pass] + hq * SROW + sc * 16, 0,
                                                                    FUSED && PHASE == 1 ? DEVICE_SCOPE : 0);
                     } else {
 #pragma unroll
                         for (int i = 0; i < 32 / RPI; ++i) {
                             const int m = wrow + mb * 32 + i * RPI + sr;
                             if (m < em_end)
-                                *reinterpret_cast<u32x4*>(a.y + (long long)mapped_row(a, m) * a.d + ug * 256 + (wn & 1) * 128 + hq * 64 + sc * 8) = v[i];
+                                *reinterpret_cast<u32x4*>(a.g2.O + (long long)mapped_row(a, m) * a.g2.ldo + ug * 256 + (wn & 1) * 128 + hq * 64 + sc * 8) = v[i];
                         }
                     }
+                }
                 }
                 __builtin_amdgcn_sched_barrier(0);     // one row block at a time: keeps the accumulator read-out short-lived
             }
@@ -1007,11 +1065,11 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
     }
 }
 
-template <int PHASE, bool GATHER>
+template <int PHASE, bool GATHER, int EPI = 0>
 __global__ __launch_bounds__(512, 1)
 void ffn_adaptive_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    ffn_adaptive_body<PHASE, GATHER, false>(a, smem);
+    ffn_adaptive_body<PHASE, GATHER, false, EPI>(a, smem);
 }
 
 // Both phases in one launch: a workgroup works through the phase-1 tiles until none is left to hand out, then
@@ -1102,10 +1160,10 @@ moe_status launch_gemm(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     return k.done();
 }
 
-template <int PHASE, bool GATHER>
-moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s) {
+template <int PHASE, bool GATHER, int EPI = 0>
+moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s, const char* name = nullptr) {
     static moe::DeviceOnce attr;
-    auto kern = ffn_adaptive_kernel<PHASE, GATHER>;
+    auto kern = ffn_adaptive_kernel<PHASE, GATHER, EPI>;
     int dev;
     if (attr.needed(dev)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ADAPTIVE_LDS);
@@ -1114,7 +1172,7 @@ moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s)
     }
     const long long slots = num_cus();
     const int grid = (int)(max_tiles < slots ? max_tiles : slots);
-    moe::LaunchScope k(PHASE == 1 ? "ffn_gemm1_kernel" : "ffn_gemm2_kernel", s);
+    moe::LaunchScope k(name ? name : (PHASE == 1 ? "ffn_gemm1_kernel" : "ffn_gemm2_kernel"), s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ADAPTIVE_LDS, s, a);
     return k.done();
 }
@@ -1237,6 +1295,14 @@ extern "C" moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t*
     a.ready = (int*)(plan + PLAN_HDR + plan_capacity(M));
     a.d = d; a.f = f;
     a.row_map = row_map; a.row_gate = row_gate;
+    a.queues1 = (int*)(plan + 1);
+    a.g2.A = a.h; a.g2.lda = f;
+    a.g2.B = (const __bf16*)w_down; a.g2.ldb = f; a.g2.strideB = (long long)d * f;
+    a.g2.O = a.y; a.g2.ldo = d;
+    a.g2.K = f; a.g2.NU = d / 256;
+    a.g2.etab = nullptr;
+    a.g2.queues = (int*)(plan + 3);
+    a.dh = nullptr; a.lddh = 0; a.dgu = nullptr;
     a.panel1 = panel_width(f / 128, (size_t)2 * d * f * 2, (size_t)256 * d * 2);
     a.panel2 = panel_width(d / 256, (size_t)d * f * 2, (size_t)256 * f * 2);
     if (const int forced = g_force_panel.load(std::memory_order_relaxed)) a.panel1 = a.panel2 = forced;
