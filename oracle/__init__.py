@@ -183,3 +183,4 @@ def slice_table(ids: np.ndarray, E: int, r: int, traffic: np.ndarray, perms: np.
 
 from .ffn import expert_ffn_sliced, expert_ffn_sliced_mapped, decode_bf16, decode_e4m3, dequant_block128  # noqa: E402,F401
 from .combine import combine_topk_sum  # noqa: E402,F401
+from .ffn_backward import expert_ffn_backward_sliced  # noqa: E402,F401
