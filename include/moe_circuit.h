@@ -249,6 +249,34 @@ moe_status moe_expert_ffn_sliced_mapped(const void* x, const int32_t* offsets, i
                                         void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_expert_ffn_backward_sliced -- Section 2.1: in training the dispatch -> compute -> combine
+ * exchange is repeated for the gradients (the backward pass doubles the all-to-alls of a layer), so
+ * the receiving rank also runs its experts backwards on the rows of every slice.  With
+ * g = x Wg_e^T, u = x Wu_e^T, s = silu(g), h = s * u (the forward pass of moe_expert_ffn_sliced)
+ * and dy the gradient with respect to y, for every row m of every group:
+ *     dh = dy Wd_e ;  du = dh * s ;  dg = dh * u * silu'(g),  silu'(z) = sig(z) (1 + z (1 - sig(z)))
+ *     dx[m] = dg Wg_e + du Wu_e
+ * and for every local expert e, summed over its rows in all slices:
+ *     dw_down[e] = dy^T h  [d][f] ;  dw_gate[e] = dg^T x  [f][d] ;  dw_up[e] = du^T x  [f][d]
+ * bf16 inputs, fp32 accumulation; dh, dg, du and h are rounded to bf16 once (g and u are recomputed
+ * from x, nothing is kept from the forward call), the outputs are bf16.
+ *   x, dy      in   bf16 [M][d]   grouped rows as in moe_expert_ffn_sliced
+ *   offsets    in   int32 [S*E_loc + 1]
+ *   w_gate, w_up in bf16 [E_loc][f][d], w_down in bf16 [E_loc][d][f]   (bf16 weights only)
+ *   dx         out  bf16 [M][d]; rows >= offsets[last] are left untouched
+ *   dw_gate, dw_up out bf16 [E_loc][f][d], dw_down out bf16 [E_loc][d][f], overwritten (an expert
+ *                   without rows gets zeros)
+ *   workspace       moe_ffn_backward_workspace_bytes(M, E_loc, d, f) bytes
+ * Limits: d % 256 == 0, f % 128 == 0, f >= 256, S*E_loc <= 65536, E_loc <= 4096, d*f < 2^30,
+ * M < about 4 million rows (MOE_ERR_UNSUPPORTED_SHAPE otherwise); every pointer 16-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+size_t     moe_ffn_backward_workspace_bytes(int M, int E_loc, int d, int f);
+moe_status moe_expert_ffn_backward_sliced(const void* x, const void* dy, const int32_t* offsets, int M, int S, int E_loc,
+                                          int d, int f, const void* w_gate, const void* w_up, const void* w_down,
+                                          void* dx, void* dw_gate, void* dw_up, void* dw_down,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * moe_combine_topk_sum -- Section 2.1 (combine): the expert results travel back to the rank that
  * owns the tokens, where each token's output is the router-weighted sum over its topk experts:
  *     out[t] = sum_{j < topk} gate[t][j] * y[row_of[t][j]]

@@ -32,6 +32,7 @@ EXPORTS = [
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped", "moe_ffn_tile_override",
     "moe_slice_table_static", "moe_decompose_profile", "moe_combine_topk_sum",
+    "moe_ffn_backward_workspace_bytes", "moe_expert_ffn_backward_sliced",
 ]
 
 _lib = None
@@ -107,6 +108,10 @@ def load():
     L.moe_ffn_expanded_weights_bytes.restype = sz
     L.moe_expert_ffn_sliced.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moe_expert_ffn_sliced.restype = ci
+    L.moe_ffn_backward_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    L.moe_ffn_backward_workspace_bytes.restype = sz
+    L.moe_expert_ffn_backward_sliced.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_expert_ffn_backward_sliced.restype = ci
     L.moe_combine_topk_sum.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     L.moe_combine_topk_sum.restype = ci
     L.moe_ffn_tile_override.argtypes = [ci, ci, ci]
@@ -366,6 +371,28 @@ def moe_expert_ffn_sliced(x, offsets, S: int, E_loc: int, w_gate, w_up, w_down, 
                                         _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(y), _ptr(workspace),
                                         workspace.numel(), _stream()), "moe_expert_ffn_sliced")
     return y
+
+
+def moe_expert_ffn_backward_sliced(x, dy, offsets, S: int, E_loc: int, w_gate, w_up, w_down, workspace=None):
+    """x, dy bf16 [M][d]; bf16 weights -> dict(dx [M][d], dw_gate, dw_up [E_loc][f][d], dw_down [E_loc][d][f])."""
+    import torch
+    for name, t in (("x", x), ("dy", dy), ("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
+        _dev_check(t, torch.bfloat16, name)
+    _dev_check(offsets, torch.int32, "offsets")
+    M, d = x.shape
+    f = w_gate.shape[1]
+    if tuple(dy.shape) != (M, d) or tuple(w_gate.shape) != (E_loc, f, d) or tuple(w_up.shape) != (E_loc, f, d) or tuple(w_down.shape) != (E_loc, d, f):
+        raise MoeError("shapes must be x, dy [M][d]; w_gate, w_up [E_loc][f][d]; w_down [E_loc][d][f]")
+    if offsets.numel() != S * E_loc + 1:
+        raise MoeError("offsets must have S*E_loc+1 entries")
+    out = dict(dx=torch.empty_like(x), dw_gate=torch.empty_like(w_gate), dw_up=torch.empty_like(w_up), dw_down=torch.empty_like(w_down))
+    need = int(load().moe_ffn_backward_workspace_bytes(M, E_loc, d, f))
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=x.device)
+    _check(load().moe_expert_ffn_backward_sliced(_ptr(x), _ptr(dy), _ptr(offsets), M, S, E_loc, d, f, _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                                 _ptr(out["dx"]), _ptr(out["dw_gate"]), _ptr(out["dw_up"]), _ptr(out["dw_down"]),
+                                                 _ptr(workspace), workspace.numel(), _stream()), "moe_expert_ffn_backward_sliced")
+    return out
 
 
 def moe_combine_topk_sum(y, row_of, gate=None, out=None):

@@ -1212,6 +1212,135 @@ moe_status launch_both(const FfnArgs& a, long long max_blocks, hipStream_t s) {
     return launch_gemm<2, ROWS, FP8>(a, max_blocks * (a.d / BN), s);
 }
 
+// ---------------------------------------------------------------------------------- backward pass: helper kernels
+constexpr int BWD_GEMMS = 6;                   // launches of the matrix kernels per backward call (each owns 8 queue counters)
+constexpr int BWD_KPAD = 128, BWD_KMIN = 256;  // an expert's rows are padded to whole pairs of 64-wide K slabs, four slabs at least
+
+__host__ __device__ inline int bwd_kpad(int rows) {
+    const int k = (rows + BWD_KPAD - 1) / BWD_KPAD * BWD_KPAD;
+    return k < BWD_KMIN ? BWD_KMIN : k;
+}
+
+// One workgroup.  Expert-major numbering of the schedule's rows (the weight gradients contract over all rows of an
+// expert, which lie in one group per slice): expert e owns columns k0_e .. k0_e + K_e - 1 of the transposed operands,
+// K_e = its row count padded as above; src_row[c] = schedule row behind column c, or -1 for padding.
+// etab[e] = (k0_e, K_e, e * f, 0).  Also clears the tile queue counters of the launches that follow.
+__global__ __launch_bounds__(PLAN_THREADS)
+void bwd_prep_kernel(const int32_t* __restrict__ offsets, int S, int e_loc, int M, int f, int cols_cap, int4* __restrict__ etab,
+                     int* __restrict__ src_row, int* __restrict__ counters, int32_t* __restrict__ w_offsets) {
+    __shared__ int k0_of[MAX_GROUPS / 16];      // (e_loc <= 4096)
+    const int tid = threadIdx.x;
+    auto bound = [&](int g) { return min(max(offsets[g], 0), M); };
+    for (int i = tid; i < cols_cap; i += PLAN_THREADS) src_row[i] = -1;
+    for (int i = tid; i < BWD_GEMMS * 8; i += PLAN_THREADS) counters[i] = 0;
+    for (int e = tid; e <= e_loc; e += PLAN_THREADS) w_offsets[e] = e * f;      // row groups of the weight gradients: f rows per expert
+    for (int e = tid; e < e_loc; e += PLAN_THREADS) {
+        int rows = 0;
+        for (int sl = 0; sl < S; ++sl) { const int g = sl * e_loc + e; rows += max(bound(g + 1) - bound(g), 0); }
+        k0_of[e] = bwd_kpad(rows);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < e_loc; ++e) { const int k = k0_of[e]; etab[e] = make_int4(run, k, e * f, 0); k0_of[e] = run; run += k; }
+    }
+    __syncthreads();
+    // one wavefront per expert at a time walks its groups in slice order
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int e = wave; e < e_loc; e += PLAN_THREADS / 64) {
+        int base = k0_of[e];
+        for (int sl = 0; sl < S; ++sl) {
+            const int g = sl * e_loc + e;
+            const int lo = bound(g), n = max(bound(g + 1) - lo, 0);
+            for (int r = lane; r < n; r += 64)
+                if (base + r < cols_cap) src_row[base + r] = lo + r;
+            base += n;
+        }
+    }
+}
+
+// dst[c][col] (pitch ldd, c < C) = src[src_row[col]][c] (pitch lds_), zero where src_row[col] < 0: the rows of a
+// row-major operand become the K-contiguous columns of its transpose, in expert-major order.  64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256)
+void bwd_gather_transpose_kernel(const __bf16* __restrict__ src, int lds_, int C, const int* __restrict__ src_row, int cols,
+                                 __bf16* __restrict__ dst, long long ldd) {
+    __shared__ unsigned short tile[64][66];
+    const int col0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const unsigned short* s16 = reinterpret_cast<const unsigned short*>(src);
+    for (int r = ty; r < 64; r += 4) {
+        const int col = col0 + r;
+        const int m = col < cols ? src_row[col] : -1;
+        tile[r][tx] = (m >= 0 && c0 + tx < C) ? s16[(size_t)m * lds_ + c0 + tx] : (unsigned short)0;
+    }
+    __syncthreads();
+    unsigned short* d16 = reinterpret_cast<unsigned short*>(dst);
+    for (int r = ty; r < 64; r += 4) {
+        const int c = c0 + r;
+        if (c < C && col0 + tx < cols) d16[(size_t)c * ldd + col0 + tx] = tile[tx][r];
+    }
+}
+
+__global__ void bwd_zero_kernel(unsigned int* __restrict__ p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// Batched transpose: dst[b][c][coff + r] (pitch ldd, slices of dstride elements) = src[b][r][c] (R x C, contiguous);
+// rows c in C .. Cpad-1 of dst are zero-filled over the same column range.
+__global__ __launch_bounds__(256)
+void bwd_transpose_kernel(const __bf16* __restrict__ src, int R, int C, int Cpad, __bf16* __restrict__ dst, long long ldd,
+                          long long dstride, int coff) {
+    __shared__ unsigned short tile[64][66];
+    const int b = blockIdx.z;
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const unsigned short* s16 = reinterpret_cast<const unsigned short*>(src) + (size_t)b * R * C;
+    for (int r = ty; r < 64; r += 4)
+        tile[r][tx] = (r0 + r < R && c0 + tx < C) ? s16[(size_t)(r0 + r) * C + c0 + tx] : (unsigned short)0;
+    __syncthreads();
+    unsigned short* d16 = reinterpret_cast<unsigned short*>(dst) + (size_t)b * dstride;
+    for (int r = ty; r < 64; r += 4) {
+        const int c = c0 + r;
+        if (c < Cpad && r0 + tx < R) d16[(size_t)c * ldd + coff + r0 + tx] = tile[tx][r];
+    }
+}
+
+inline size_t al256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+struct BwdLayout {                              // byte offsets into the workspace of a backward call
+    size_t plan_rows, ready_rows, plan_w, ready_w, counters, etab, w_offsets, src_row, wdt, wgut, dh, dgu, h, tx, tdy, th, tdg, tdu, dwdt, total;
+    int f_pad, cols_cap;
+};
+BwdLayout bwd_layout(int M, int E_loc, int d, int f) {
+    BwdLayout L;
+    L.f_pad = (f + 255) / 256 * 256;
+    L.cols_cap = (M + BWD_KPAD - 1) / BWD_KPAD * BWD_KPAD + BWD_KMIN * E_loc;
+    const int wrows = E_loc * f;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += al256(bytes); return at; };
+    L.plan_rows = take((size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4));
+    L.ready_rows = take((size_t)plan_capacity(M) * sizeof(int));
+    L.plan_w = take((size_t)(plan_capacity(wrows) + PLAN_HDR) * sizeof(int4));
+    L.ready_w = take((size_t)plan_capacity(wrows) * sizeof(int));
+    L.counters = take((size_t)BWD_GEMMS * 8 * sizeof(int));
+    L.etab = take((size_t)E_loc * sizeof(int4));
+    L.w_offsets = take((size_t)(E_loc + 1) * sizeof(int32_t));
+    L.src_row = take((size_t)L.cols_cap * sizeof(int));
+    L.wdt = take((size_t)E_loc * L.f_pad * d * 2);
+    L.wgut = take((size_t)E_loc * d * 2 * f * 2);
+    L.dh = take((size_t)M * L.f_pad * 2);
+    L.dgu = take((size_t)M * 2 * f * 2);
+    L.h = take((size_t)M * f * 2);
+    L.tx = take((size_t)d * L.cols_cap * 2);
+    L.tdy = take((size_t)d * L.cols_cap * 2);
+    L.th = take((size_t)f * L.cols_cap * 2);
+    L.tdg = take((size_t)f * L.cols_cap * 2);
+    L.tdu = take((size_t)f * L.cols_cap * 2);
+    L.dwdt = take((size_t)E_loc * f * d * 2);
+    L.total = o;
+    return L;
+}
+
 }  // namespace
 
 extern "C" size_t moe_ffn_workspace_bytes(int M, int d, int f) {
@@ -1332,4 +1461,142 @@ extern "C" moe_status moe_expert_ffn_sliced(const void* x, const int32_t* offset
                                             void* workspace, size_t workspace_bytes, void* hip_stream) {
     return moe_expert_ffn_sliced_mapped(x, offsets, M, S, E_loc, d, f, weight_format, w_gate, w_up, w_down, s_gate, s_up,
                                         s_down, nullptr, nullptr, y, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t moe_ffn_backward_workspace_bytes(int M, int E_loc, int d, int f) {
+    if (M < 0 || E_loc < 1 || d < 1 || f < 1) return 0;
+    return bwd_layout(M, E_loc, d, f).total;
+}
+
+extern "C" moe_status moe_expert_ffn_backward_sliced(const void* x, const void* dy, const int32_t* offsets, int M, int S, int E_loc,
+                                                     int d, int f, const void* w_gate, const void* w_up, const void* w_down,
+                                                     void* dx, void* dw_gate, void* dw_up, void* dw_down, void* workspace,
+                                                     size_t workspace_bytes, void* hip_stream) {
+    if (M < 0 || S < 0 || E_loc < 1 || d < 1 || f < 1 || !offsets) return MOE_ERR_INVALID_ARG;
+    if (!w_gate || !w_up || !w_down || !dw_gate || !dw_up || !dw_down) return MOE_ERR_INVALID_ARG;
+    if (d % 256 != 0 || f % 128 != 0 || f < 256) return MOE_ERR_UNSUPPORTED_SHAPE;
+    const long long G = (long long)S * E_loc;
+    if (G > MAX_GROUPS || E_loc > MAX_GROUPS / 16) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (d > (1 << 22) || f > (1 << 21) || (long long)d * f >= (1LL << 30)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (M > 0 && (!x || !dy || !dx)) return MOE_ERR_INVALID_ARG;
+    if ((((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx | (uintptr_t)w_gate | (uintptr_t)w_up | (uintptr_t)w_down | (uintptr_t)dw_gate |
+          (uintptr_t)dw_up | (uintptr_t)dw_down | (uintptr_t)workspace) & 15) != 0)
+        return MOE_ERR_INVALID_ARG;
+    const BwdLayout L = bwd_layout(M, E_loc, d, f);
+    // 32-bit byte offsets inside one 256-row tile of the transposed operands (row pitch = cols_cap)
+    if ((long long)L.cols_cap * 512 * 2 >= (1LL << 32)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (!workspace || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    int4* plan_rows = (int4*)(ws + L.plan_rows);
+    int4* plan_w = (int4*)(ws + L.plan_w);
+    int* counters = (int*)(ws + L.counters);
+    int4* etab = (int4*)(ws + L.etab);
+    int* src_row = (int*)(ws + L.src_row);
+    __bf16 *wdt = (__bf16*)(ws + L.wdt), *wgut = (__bf16*)(ws + L.wgut), *dh = (__bf16*)(ws + L.dh), *dgu = (__bf16*)(ws + L.dgu);
+    __bf16 *h = (__bf16*)(ws + L.h), *tx = (__bf16*)(ws + L.tx), *tdy = (__bf16*)(ws + L.tdy), *th = (__bf16*)(ws + L.th);
+    __bf16 *tdg = (__bf16*)(ws + L.tdg), *tdu = (__bf16*)(ws + L.tdu), *dwdt = (__bf16*)(ws + L.dwdt);
+    const int wrows = E_loc * f;
+    moe_status st;
+
+    // ---- plans (row blocks of the schedule; row blocks of the weight gradients: one group of f rows per expert),
+    //      expert-major column numbering, transposed weights
+    {
+        moe::LaunchScope k("ffn_plan_kernel", s);
+        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, (int)G, E_loc, M, 256, plan_capacity(M), plan_rows,
+                           (int*)(ws + L.ready_rows));
+        if ((st = k.done()) != MOE_OK) return st;
+    }
+    {
+        moe::LaunchScope k("bwd_prep_kernel", s);
+        hipLaunchKernelGGL(bwd_prep_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, S, E_loc, M, f, L.cols_cap, etab, src_row, counters,
+                           (int32_t*)(ws + L.w_offsets));
+        if ((st = k.done()) != MOE_OK) return st;
+    }
+    {
+        moe::LaunchScope k("bwd_transpose_kernel", s);
+        const dim3 blk(256);
+        // w_down [E][d][f] -> wdt [E][f_pad][d] (rows f .. f_pad-1 zero)
+        hipLaunchKernelGGL(bwd_transpose_kernel, dim3((d + 63) / 64, (L.f_pad + 63) / 64, E_loc), blk, 0, s, (const __bf16*)w_down, d, f,
+                           L.f_pad, wdt, (long long)d, (long long)L.f_pad * d, 0);
+        // w_gate, w_up [E][f][d] -> wgut [E][d][2f] = [gate^T | up^T]
+        hipLaunchKernelGGL(bwd_transpose_kernel, dim3((f + 63) / 64, (d + 63) / 64, E_loc), blk, 0, s, (const __bf16*)w_gate, f, d, d, wgut,
+                           (long long)2 * f, (long long)d * 2 * f, 0);
+        hipLaunchKernelGGL(bwd_transpose_kernel, dim3((f + 63) / 64, (d + 63) / 64, E_loc), blk, 0, s, (const __bf16*)w_up, f, d, d, wgut,
+                           (long long)2 * f, (long long)d * 2 * f, f);
+        if ((st = k.done()) != MOE_OK) return st;
+    }
+    if (M == 0 || G == 0) {
+        // no rows: the weight gradients are zero, dx is empty
+        moe::LaunchScope k("bwd_zero_kernel", s);
+        const size_t words = (size_t)E_loc * f * d / 2;
+        for (void* p : {dw_gate, dw_up, dw_down}) hipLaunchKernelGGL(bwd_zero_kernel, dim3(1024), dim3(256), 0, s, (unsigned int*)p, words);
+        return k.done();
+    }
+
+    FfnArgs a;
+    a.x = (const __bf16*)x; a.h = h; a.y = nullptr;
+    a.wg = w_gate; a.wu = w_up; a.wd = w_down;
+    a.sg = a.su = a.sd = nullptr;
+    a.plan = plan_rows;
+    a.ready = (int*)(ws + L.ready_rows);
+    a.d = d; a.f = f;
+    a.row_map = nullptr; a.row_gate = nullptr;
+    a.panel1 = a.panel2 = 1 << 20;
+    a.dh = dh; a.lddh = L.f_pad; a.dgu = dgu;
+    a.queues1 = counters + 8;
+    a.g2.etab = nullptr;
+    const long long row_blocks = M / 256 + G;
+
+    // ---- dh = dy Wd: rows x f_pad, K = d
+    a.g2.A = (const __bf16*)dy; a.g2.lda = d;
+    a.g2.B = wdt; a.g2.ldb = d; a.g2.strideB = (long long)L.f_pad * d;
+    a.g2.O = dh; a.g2.ldo = L.f_pad;
+    a.g2.K = d; a.g2.NU = L.f_pad / 256;
+    a.g2.queues = counters + 0;
+    if ((st = launch_adaptive<2, false, 0>(a, row_blocks * a.g2.NU, s, "ffn_bwd_dh_kernel")) != MOE_OK) return st;
+    // ---- g, u recomputed; dg, du, h
+    if ((st = launch_adaptive<1, false, 1>(a, row_blocks * (f / 128), s, "ffn_bwd_act_kernel")) != MOE_OK) return st;
+    // ---- dx = [dg | du] [Wg ; Wu]: rows x d, K = 2f
+    a.g2.A = dgu; a.g2.lda = 2 * f;
+    a.g2.B = wgut; a.g2.ldb = 2 * f; a.g2.strideB = (long long)d * 2 * f;
+    a.g2.O = (__bf16*)dx; a.g2.ldo = d;
+    a.g2.K = 2 * f; a.g2.NU = d / 256;
+    a.g2.queues = counters + 16;
+    if ((st = launch_adaptive<2, false, 0>(a, row_blocks * a.g2.NU, s, "ffn_bwd_dx_kernel")) != MOE_OK) return st;
+
+    // ---- transposed, expert-major copies of the operands of the weight gradients
+    {
+        moe::LaunchScope k("bwd_gather_transpose_kernel", s);
+        const int cb = (L.cols_cap + 63) / 64;
+        hipLaunchKernelGGL(bwd_gather_transpose_kernel, dim3(cb, (d + 63) / 64), dim3(256), 0, s, (const __bf16*)x, d, d, src_row, L.cols_cap, tx, (long long)L.cols_cap);
+        hipLaunchKernelGGL(bwd_gather_transpose_kernel, dim3(cb, (d + 63) / 64), dim3(256), 0, s, (const __bf16*)dy, d, d, src_row, L.cols_cap, tdy, (long long)L.cols_cap);
+        hipLaunchKernelGGL(bwd_gather_transpose_kernel, dim3(cb, (f + 63) / 64), dim3(256), 0, s, (const __bf16*)h, f, f, src_row, L.cols_cap, th, (long long)L.cols_cap);
+        hipLaunchKernelGGL(bwd_gather_transpose_kernel, dim3(cb, (f + 63) / 64), dim3(256), 0, s, (const __bf16*)dgu, 2 * f, f, src_row, L.cols_cap, tdg, (long long)L.cols_cap);
+        hipLaunchKernelGGL(bwd_gather_transpose_kernel, dim3(cb, (f + 63) / 64), dim3(256), 0, s, (const __bf16*)dgu + f, 2 * f, f, src_row, L.cols_cap, tdu, (long long)L.cols_cap);
+        if ((st = k.done()) != MOE_OK) return st;
+    }
+    // ---- weight gradients: one group of f rows per expert, K = the expert's (padded) row count
+    {
+        moe::LaunchScope k("ffn_plan_kernel", s);
+        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, (const int32_t*)(ws + L.w_offsets), E_loc, E_loc, wrows, 256,
+                           plan_capacity(wrows), plan_w, (int*)(ws + L.ready_w));
+        if ((st = k.done()) != MOE_OK) return st;
+    }
+    a.plan = plan_w;
+    a.g2.etab = etab;
+    a.g2.lda = L.cols_cap; a.g2.ldb = L.cols_cap; a.g2.strideB = 0;
+    a.g2.ldo = d; a.g2.K = BWD_KMIN; a.g2.NU = d / 256;
+    const long long w_blocks = wrows / 256 + E_loc;
+    struct { const __bf16 *A, *B; __bf16* O; int q; const char* name; } wg[3] = {
+        {tdg, tx, (__bf16*)dw_gate, 24, "ffn_bwd_dwg_kernel"}, {tdu, tx, (__bf16*)dw_up, 32, "ffn_bwd_dwu_kernel"}, {th, tdy, dwdt, 40, "ffn_bwd_dwd_kernel"}};
+    for (int i = 0; i < 3; ++i) {
+        a.g2.A = wg[i].A; a.g2.B = wg[i].B; a.g2.O = wg[i].O; a.g2.queues = counters + wg[i].q;
+        if ((st = launch_adaptive<2, false, 0>(a, w_blocks * a.g2.NU, s, wg[i].name)) != MOE_OK) return st;
+    }
+    // dWd^T [E][f][d] -> dw_down [E][d][f]
+    moe::LaunchScope k("bwd_transpose_kernel", s);
+    hipLaunchKernelGGL(bwd_transpose_kernel, dim3((f + 63) / 64, (d + 63) / 64, E_loc), dim3(256), 0, s, dwdt, f, d, d, (__bf16*)dw_down,
+                       (long long)f, (long long)d * f, 0);
+    return k.done();
 }

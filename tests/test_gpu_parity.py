@@ -675,6 +675,70 @@ def test_ffn_mapped(lib, dtype, tile_rows):
         lib.moe_ffn_tile_override()
 
 
+# ------------------------------------------------------------------------------ FFN backward
+def check_backward(lib, E_loc, d, f, M, S, seed, what, spare=0, empty_frac=0.15):
+    W = workloads.ffn_weights(E_loc, d, f, seed=seed)
+    x = workloads.activations(M + spare, d, seed=seed + 1)
+    dy = workloads.activations(M + spare, d, seed=seed + 2)
+    offsets = workloads.random_offsets(S * E_loc, M, seed=seed + 3, empty_frac=empty_frac)
+    w = upload_weights(W)
+    out = lib.moe_expert_ffn_backward_sliced(dev_bf16(x), dev_bf16(dy), dev(offsets), S, E_loc, w["w_gate"], w["w_up"], w["w_down"])
+    torch.cuda.synchronize()
+    dx, dWg, dWu, dWd = oracle.expert_ffn_backward_sliced(x, dy, offsets, E_loc, W)
+    if M > 0:
+        check_ffn_error(ffn_error(host_bf16_bits(out["dx"])[:M], dx, offsets), "bf16", what + " dx")
+    for name, ref in (("dw_gate", dWg), ("dw_up", dWu), ("dw_down", dWd)):
+        got = oracle.decode_bf16(host_bf16_bits(out[name]))
+        for e in range(E_loc):
+            scale = np.abs(ref[e]).max()
+            if scale == 0:
+                assert not got[e].any(), (name, e)
+                continue
+            check_ffn_error(float(np.abs(got[e] - ref[e]).max() / scale), "bf16", "%s %s[%d]" % (what, name, e))
+    return out
+
+
+@pytest.mark.parametrize("E_loc,d,f,M,S", [(1, 256, 256, 300, 1), (2, 256, 384, 1500, 3), (4, 512, 640, 5000, 4), (3, 256, 1408, 900, 2)])
+def test_ffn_backward_small(lib, E_loc, d, f, M, S):
+    """dx for every row and the three weight gradients of every expert against the float64 chain rule."""
+    say("ffn backward small", E_loc, d, f, M, S)
+    check_backward(lib, E_loc, d, f, M, S, seed=d + f + M, what="small", spare=5)
+
+
+def test_ffn_backward_edge_cases(lib):
+    say("ffn backward edge cases")
+    # an expert without rows (zero weight gradients), a single row, no rows at all
+    E_loc, d, f = 3, 256, 256
+    W = workloads.ffn_weights(E_loc, d, f, seed=3)
+    w = upload_weights(W)
+    x = workloads.activations(40, d, seed=4)
+    dy = workloads.activations(40, d, seed=5)
+    for sizes in ([40, 0, 0], [0, 1, 0], [0, 0, 0], [13, 0, 27]):
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        out = lib.moe_expert_ffn_backward_sliced(dev_bf16(x), dev_bf16(dy), dev(off), 1, E_loc, w["w_gate"], w["w_up"], w["w_down"])
+        torch.cuda.synchronize()
+        dx, dWg, dWu, dWd = oracle.expert_ffn_backward_sliced(x, dy, off, E_loc, W)
+        n = int(off[-1])
+        if n:
+            check_ffn_error(ffn_error(host_bf16_bits(out["dx"])[:n], dx, off), "bf16", str(sizes))
+        for name, ref in (("dw_gate", dWg), ("dw_up", dWu), ("dw_down", dWd)):
+            got = oracle.decode_bf16(host_bf16_bits(out[name]))
+            for e in range(E_loc):
+                if sizes[e] == 0:
+                    assert not got[e].any(), (sizes, name, e)
+                else:
+                    assert np.abs(got[e] - ref[e]).max() <= FFN_GUARD["bf16"] * np.abs(ref[e]).max(), (sizes, name, e)
+    with pytest.raises(lib.MoeError):                                    # f below the smallest supported width
+        lib.moe_expert_ffn_backward_sliced(dev_bf16(x), dev_bf16(dy), dev(off), 1, E_loc, w["w_gate"][:, :128].contiguous(),
+                                           w["w_up"][:, :128].contiguous(), w["w_down"][:, :, :128].contiguous())
+
+
+def test_ffn_backward_many_tiles(lib):
+    """A schedule on which every workgroup runs several tiles in each of the six matrix launches."""
+    say("ffn backward many tiles")
+    check_backward(lib, 4, 1536, 768, 36000, 6, seed=61, what="36000 rows")
+
+
 # ------------------------------------------------------------------------------ combine
 def combine_tolerance(y_bits, row_of, gate, ref):
     """fp32 accumulation of topk terms (2^-24 of the terms' magnitudes each) and one rounding to bf16 (2^-9 of the
