@@ -1214,35 +1214,54 @@ moe_status launch_both(const FfnArgs& a, long long max_blocks, hipStream_t s) {
 
 // ---------------------------------------------------------------------------------- backward pass: helper kernels
 constexpr int BWD_GEMMS = 6;                   // launches of the matrix kernels per backward call (each owns 8 queue counters)
-constexpr int BWD_KPAD = 128, BWD_KMIN = 256;  // an expert's rows are padded to whole pairs of 64-wide K slabs, four slabs at least
+constexpr int BWD_KPAD = 128, BWD_KMIN = 256;  // a K range is padded to whole pairs of 64-wide K slabs, four slabs at least
+constexpr int BWD_MAX_SPLIT = 16;
 
-__host__ __device__ inline int bwd_kpad(int rows) {
-    const int k = (rows + BWD_KPAD - 1) / BWD_KPAD * BWD_KPAD;
-    return k < BWD_KMIN ? BWD_KMIN : k;
+// padded row count of an expert whose rows are contracted in P parts of equal length
+__host__ __device__ inline int bwd_kpad(int rows, int P) {
+    const int unit = BWD_KPAD * P;
+    const int k = (rows + unit - 1) / unit * unit;
+    return k < BWD_KMIN * P ? BWD_KMIN * P : k;
+}
+
+// Parts the contraction of a weight gradient is split into.  The gradients have few output tiles (E_loc * f / 256 row
+// blocks times d / 256 column units) and a very long contraction (all rows of the expert): unsplit, a small layer does
+// not fill the chip and a large one runs in a few coarse rounds.  Parts produce partial sums that are added in fp32.
+int bwd_split(int M, int E_loc, int d, int f) {
+    const long long tiles = (long long)E_loc * ((f + 255) / 256) * (d / 256);
+    int P = 1;
+    while (P < BWD_MAX_SPLIT && tiles * P < 8 * 256 && (long long)M / E_loc / (2 * P) >= 1024) P *= 2;
+    return P;
 }
 
 // One workgroup.  Expert-major numbering of the schedule's rows (the weight gradients contract over all rows of an
 // expert, which lie in one group per slice): expert e owns columns k0_e .. k0_e + K_e - 1 of the transposed operands,
 // K_e = its row count padded as above; src_row[c] = schedule row behind column c, or -1 for padding.
-// etab[e] = (k0_e, K_e, e * f, 0).  Also clears the tile queue counters of the launches that follow.
+// The contraction of expert e is split into P parts ("virtual experts" v = e * P + p with partial results of their own):
+// etab[v] = (k0_e + p * K_e / P, K_e / P, v * f, 0).  Also clears the tile queue counters of the launches that follow.
 __global__ __launch_bounds__(PLAN_THREADS)
-void bwd_prep_kernel(const int32_t* __restrict__ offsets, int S, int e_loc, int M, int f, int cols_cap, int4* __restrict__ etab,
+void bwd_prep_kernel(const int32_t* __restrict__ offsets, int S, int e_loc, int M, int f, int cols_cap, int P, int4* __restrict__ etab,
                      int* __restrict__ src_row, int* __restrict__ counters, int32_t* __restrict__ w_offsets) {
     __shared__ int k0_of[MAX_GROUPS / 16];      // (e_loc <= 4096)
     const int tid = threadIdx.x;
     auto bound = [&](int g) { return min(max(offsets[g], 0), M); };
     for (int i = tid; i < cols_cap; i += PLAN_THREADS) src_row[i] = -1;
     for (int i = tid; i < BWD_GEMMS * 8; i += PLAN_THREADS) counters[i] = 0;
-    for (int e = tid; e <= e_loc; e += PLAN_THREADS) w_offsets[e] = e * f;      // row groups of the weight gradients: f rows per expert
+    for (int v = tid; v <= e_loc * P; v += PLAN_THREADS) w_offsets[v] = v * f;  // row groups of the weight gradients: f rows per part
     for (int e = tid; e < e_loc; e += PLAN_THREADS) {
         int rows = 0;
         for (int sl = 0; sl < S; ++sl) { const int g = sl * e_loc + e; rows += max(bound(g + 1) - bound(g), 0); }
-        k0_of[e] = bwd_kpad(rows);
+        k0_of[e] = bwd_kpad(rows, P);
     }
     __syncthreads();
     if (tid == 0) {
         int run = 0;
-        for (int e = 0; e < e_loc; ++e) { const int k = k0_of[e]; etab[e] = make_int4(run, k, e * f, 0); k0_of[e] = run; run += k; }
+        for (int e = 0; e < e_loc; ++e) {
+            const int k = k0_of[e], kp = k / P;
+            for (int p = 0; p < P; ++p) etab[e * P + p] = make_int4(run + p * kp, kp, (e * P + p) * f, 0);
+            k0_of[e] = run;
+            run += k;
+        }
     }
     __syncthreads();
     // one wavefront per expert at a time walks its groups in slice order
@@ -1260,24 +1279,51 @@ void bwd_prep_kernel(const int32_t* __restrict__ offsets, int S, int e_loc, int 
 }
 
 // dst[c][col] (pitch ldd, c < C) = src[src_row[col]][c] (pitch lds_), zero where src_row[col] < 0: the rows of a
-// row-major operand become the K-contiguous columns of its transpose, in expert-major order.  64 x 64 tiles through LDS.
+// row-major operand become the K-contiguous columns of its transpose, in expert-major order.  HBM bound.  64 x 64 tiles
+// through LDS; both sides move 16 bytes per thread (C and lds_ are multiples of 8, cols and ldd of 64).
 __global__ __launch_bounds__(256)
 void bwd_gather_transpose_kernel(const __bf16* __restrict__ src, int lds_, int C, const int* __restrict__ src_row, int cols,
                                  __bf16* __restrict__ dst, long long ldd) {
-    __shared__ unsigned short tile[64][66];
+    __shared__ unsigned short tile[64][72];                              // [feature][column], padded rows
     const int col0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const unsigned short* s16 = reinterpret_cast<const unsigned short*>(src);
-    for (int r = ty; r < 64; r += 4) {
-        const int col = col0 + r;
+    const int part = threadIdx.x & 7, line = threadIdx.x >> 3;           // 8 threads per 64-value line, 32 lines per pass
+    typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int r = line + 32 * p, col = col0 + r;
         const int m = col < cols ? src_row[col] : -1;
-        tile[r][tx] = (m >= 0 && c0 + tx < C) ? s16[(size_t)m * lds_ + c0 + tx] : (unsigned short)0;
+        us8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (m >= 0 && c0 + part * 8 < C) v = *reinterpret_cast<const us8*>(reinterpret_cast<const unsigned short*>(src) + (size_t)m * lds_ + c0 + part * 8);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) tile[part * 8 + k][r] = v[k];
     }
     __syncthreads();
-    unsigned short* d16 = reinterpret_cast<unsigned short*>(dst);
-    for (int r = ty; r < 64; r += 4) {
-        const int c = c0 + r;
-        if (c < C && col0 + tx < cols) d16[(size_t)c * ldd + col0 + tx] = tile[tx][r];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int c = c0 + line + 32 * p;
+        if (c < C && col0 + part * 8 < cols)
+            *reinterpret_cast<us8*>(reinterpret_cast<unsigned short*>(dst) + (size_t)c * ldd + col0 + part * 8) =
+                *reinterpret_cast<const us8*>(&tile[line + 32 * p][part * 8]);
+    }
+}
+
+// out[e][r] = sum over p of part[e * P + p][r] (n values per expert), added in fp32 in part order; 8 values per thread
+__global__ __launch_bounds__(256)
+void bwd_reduce_parts_kernel(const __bf16* __restrict__ part, int P, long long n, int E, __bf16* __restrict__ out) {
+    typedef __attribute__((ext_vector_type(8))) __bf16 b8;
+    const long long n8 = n / 8, total = n8 * E;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long e = i / n8, r = (i - e * n8) * 8;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < P; ++p) {
+            const b8 v = *reinterpret_cast<const b8*>(part + ((e * P + p) * n + r));
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[k] += (float)v[k];
+        }
+        b8 o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o[k] = (__bf16)acc[k];
+        *reinterpret_cast<b8*>(out + (e * n + r)) = o;
     }
 }
 
@@ -1308,14 +1354,15 @@ void bwd_transpose_kernel(const __bf16* __restrict__ src, int R, int C, int Cpad
 inline size_t al256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 struct BwdLayout {                              // byte offsets into the workspace of a backward call
-    size_t plan_rows, ready_rows, plan_w, ready_w, counters, etab, w_offsets, src_row, wdt, wgut, dh, dgu, h, tx, tdy, th, tdg, tdu, dwdt, total;
-    int f_pad, cols_cap;
+    size_t plan_rows, ready_rows, plan_w, ready_w, counters, etab, w_offsets, src_row, wdt, wgut, dh, dgu, h, tx, tdy, th, tdg, tdu, dwdt, part, total;
+    int f_pad, cols_cap, P;
 };
 BwdLayout bwd_layout(int M, int E_loc, int d, int f) {
     BwdLayout L;
     L.f_pad = (f + 255) / 256 * 256;
-    L.cols_cap = (M + BWD_KPAD - 1) / BWD_KPAD * BWD_KPAD + BWD_KMIN * E_loc;
-    const int wrows = E_loc * f;
+    L.P = bwd_split(M, E_loc, d, f);
+    L.cols_cap = (M + BWD_KPAD - 1) / BWD_KPAD * BWD_KPAD + BWD_KMIN * L.P * E_loc;
+    const int wrows = E_loc * L.P * f;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += al256(bytes); return at; };
     L.plan_rows = take((size_t)(plan_capacity(M) + PLAN_HDR) * sizeof(int4));
@@ -1323,8 +1370,8 @@ BwdLayout bwd_layout(int M, int E_loc, int d, int f) {
     L.plan_w = take((size_t)(plan_capacity(wrows) + PLAN_HDR) * sizeof(int4));
     L.ready_w = take((size_t)plan_capacity(wrows) * sizeof(int));
     L.counters = take((size_t)BWD_GEMMS * 8 * sizeof(int));
-    L.etab = take((size_t)E_loc * sizeof(int4));
-    L.w_offsets = take((size_t)(E_loc + 1) * sizeof(int32_t));
+    L.etab = take((size_t)E_loc * L.P * sizeof(int4));
+    L.w_offsets = take((size_t)(E_loc * L.P + 1) * sizeof(int32_t));
     L.src_row = take((size_t)L.cols_cap * sizeof(int));
     L.wdt = take((size_t)E_loc * L.f_pad * d * 2);
     L.wgut = take((size_t)E_loc * d * 2 * f * 2);
@@ -1337,6 +1384,7 @@ BwdLayout bwd_layout(int M, int E_loc, int d, int f) {
     L.tdg = take((size_t)f * L.cols_cap * 2);
     L.tdu = take((size_t)f * L.cols_cap * 2);
     L.dwdt = take((size_t)E_loc * f * d * 2);
+    L.part = take(L.P > 1 ? (size_t)E_loc * L.P * f * d * 2 : 0);
     L.total = o;
     return L;
 }
@@ -1476,7 +1524,7 @@ extern "C" moe_status moe_expert_ffn_backward_sliced(const void* x, const void* 
     if (!w_gate || !w_up || !w_down || !dw_gate || !dw_up || !dw_down) return MOE_ERR_INVALID_ARG;
     if (d % 256 != 0 || f % 128 != 0 || f < 256) return MOE_ERR_UNSUPPORTED_SHAPE;
     const long long G = (long long)S * E_loc;
-    if (G > MAX_GROUPS || E_loc > MAX_GROUPS / 16) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (G > MAX_GROUPS || E_loc > MAX_GROUPS / 16 || (long long)E_loc * BWD_MAX_SPLIT * f >= (1LL << 31)) return MOE_ERR_UNSUPPORTED_SHAPE;
     if (d > (1 << 22) || f > (1 << 21) || (long long)d * f >= (1LL << 30)) return MOE_ERR_UNSUPPORTED_SHAPE;
     if (M > 0 && (!x || !dy || !dx)) return MOE_ERR_INVALID_ARG;
     if ((((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx | (uintptr_t)w_gate | (uintptr_t)w_up | (uintptr_t)w_down | (uintptr_t)dw_gate |
@@ -1496,7 +1544,8 @@ extern "C" moe_status moe_expert_ffn_backward_sliced(const void* x, const void* 
     __bf16 *wdt = (__bf16*)(ws + L.wdt), *wgut = (__bf16*)(ws + L.wgut), *dh = (__bf16*)(ws + L.dh), *dgu = (__bf16*)(ws + L.dgu);
     __bf16 *h = (__bf16*)(ws + L.h), *tx = (__bf16*)(ws + L.tx), *tdy = (__bf16*)(ws + L.tdy), *th = (__bf16*)(ws + L.th);
     __bf16 *tdg = (__bf16*)(ws + L.tdg), *tdu = (__bf16*)(ws + L.tdu), *dwdt = (__bf16*)(ws + L.dwdt);
-    const int wrows = E_loc * f;
+    __bf16* part = (__bf16*)(ws + L.part);
+    const int P = L.P, wrows = E_loc * P * f;
     moe_status st;
 
     // ---- plans (row blocks of the schedule; row blocks of the weight gradients: one group of f rows per expert),
@@ -1509,7 +1558,7 @@ extern "C" moe_status moe_expert_ffn_backward_sliced(const void* x, const void* 
     }
     {
         moe::LaunchScope k("bwd_prep_kernel", s);
-        hipLaunchKernelGGL(bwd_prep_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, S, E_loc, M, f, L.cols_cap, etab, src_row, counters,
+        hipLaunchKernelGGL(bwd_prep_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, offsets, S, E_loc, M, f, L.cols_cap, P, etab, src_row, counters,
                            (int32_t*)(ws + L.w_offsets));
         if ((st = k.done()) != MOE_OK) return st;
     }
@@ -1579,7 +1628,7 @@ extern "C" moe_status moe_expert_ffn_backward_sliced(const void* x, const void* 
     // ---- weight gradients: one group of f rows per expert, K = the expert's (padded) row count
     {
         moe::LaunchScope k("ffn_plan_kernel", s);
-        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, (const int32_t*)(ws + L.w_offsets), E_loc, E_loc, wrows, 256,
+        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, (const int32_t*)(ws + L.w_offsets), E_loc * P, E_loc * P, wrows, 256,
                            plan_capacity(wrows), plan_w, (int*)(ws + L.ready_w));
         if ((st = k.done()) != MOE_OK) return st;
     }
@@ -1587,12 +1636,19 @@ extern "C" moe_status moe_expert_ffn_backward_sliced(const void* x, const void* 
     a.g2.etab = etab;
     a.g2.lda = L.cols_cap; a.g2.ldb = L.cols_cap; a.g2.strideB = 0;
     a.g2.ldo = d; a.g2.K = BWD_KMIN; a.g2.NU = d / 256;
-    const long long w_blocks = wrows / 256 + E_loc;
+    const long long w_blocks = wrows / 256 + E_loc * P;
     struct { const __bf16 *A, *B; __bf16* O; int q; const char* name; } wg[3] = {
         {tdg, tx, (__bf16*)dw_gate, 24, "ffn_bwd_dwg_kernel"}, {tdu, tx, (__bf16*)dw_up, 32, "ffn_bwd_dwu_kernel"}, {th, tdy, dwdt, 40, "ffn_bwd_dwd_kernel"}};
     for (int i = 0; i < 3; ++i) {
-        a.g2.A = wg[i].A; a.g2.B = wg[i].B; a.g2.O = wg[i].O; a.g2.queues = counters + wg[i].q;
+        a.g2.A = wg[i].A; a.g2.B = wg[i].B; a.g2.O = P > 1 ? part : wg[i].O; a.g2.queues = counters + wg[i].q;
         if ((st = launch_adaptive<2, false, 0>(a, w_blocks * a.g2.NU, s, wg[i].name)) != MOE_OK) return st;
+        if (P > 1) {                                                     // partial sums of the P parts -> the gradient
+            moe::LaunchScope k("bwd_reduce_parts_kernel", s);
+            const long long n = (long long)f * d;
+            const int blocks = (int)std::min<long long>((n / 8 * E_loc + 255) / 256, 8LL * num_cus());
+            hipLaunchKernelGGL(bwd_reduce_parts_kernel, dim3(blocks), dim3(256), 0, s, part, P, n, E_loc, wg[i].O);
+            if ((st = k.done()) != MOE_OK) return st;
+        }
     }
     // dWd^T [E][f][d] -> dw_down [E][d][f]
     moe::LaunchScope k("bwd_transpose_kernel", s);
