@@ -405,6 +405,24 @@ def ffn_entry(moe, torch, wl, reps, kernels):
     return e
 
 
+def backward_entry(moe, torch, workloads, wl, reps):
+    """The backward pass of the same schedule (second workload: dx and the three weight gradients per expert; bf16 weights
+    only): time per call and per kernel; algorithmic flop = 12*d*f*M (dh 2, dx 4, weight gradients 6), executed 16*d*f*M
+    (the gate / up projections are recomputed)."""
+    cfg, M = wl.cfg, wl.M
+    if cfg.weight_dtype != "bf16":
+        return None
+    dy = workloads.activations_on_device(M, cfg.d, cfg.seed + 9, wl.x.device)
+    ws = torch.empty((int(moe.load().moe_ffn_backward_workspace_bytes(M, cfg.E_loc, cfg.d, cfg.f)),), dtype=torch.uint8, device=wl.x.device)
+    fn = lambda: moe.moe_expert_ffn_backward_sliced(wl.x, dy, wl.offsets, wl.S, cfg.E_loc, wl.w["w_gate"], wl.w["w_up"], wl.w["w_down"], workspace=ws)
+    times, dt = kernel_times(moe, torch, fn, reps)
+    gemm = sum(v for k, v in times.items() if k.startswith("ffn_bwd_"))
+    alg = 12.0 * cfg.d * cfg.f * M
+    return {"rows": M, "call_us": dt * 1e6, "tflops_algorithmic": alg / dt / 1e12, "frac_mfma_peak_algorithmic": alg / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "matrix_kernels_us": gemm, "tflops_executed_in_matrix_kernels": 16.0 * cfg.d * cfg.f * M / gemm / 1e6,
+            "workspace_GB": ws.numel() / 1e9, "kernels_us": times}
+
+
 def phase_figures(cfg, M, g1_us, g2_us):
     f1, f2 = 4.0 * cfg.d * cfg.f * M, 2.0 * cfg.d * cfg.f * M
     return {"phase1_us": g1_us, "phase2_us": g2_us, "phase1_tflops": f1 / g1_us / 1e6, "phase2_tflops": f2 / g2_us / 1e6,
@@ -524,6 +542,7 @@ def main():
         ex["ffn_by_config"] = {cfg.name: ffn_figures(cfg, M, wl.S, gemm_us, other_us)}
         ex["ffn_by_config"][cfg.name]["one_launch_per_phase"] = result["ffn_one_launch_per_phase"]
         ex["vendor_gemm_same_shape"] = vendor_gemm(torch, wl)
+        ex["backward_by_config"] = {cfg.name: backward_entry(moe, torch, workloads, wl, 3)}
         ex.update(ffn_granularity(moe, torch, np, wl))
         ex["makespan_model_us"] = makespan_extras(moe, np, cfg, wl.traffic, wl.g_out, wl.b_out, ex["expert_time_us_vs_rows"])
         x_sample, sample_rows = None, None
@@ -540,6 +559,9 @@ def main():
             other_wl = Workload(moe, torch, np, workloads, workloads.CONFIGS[name], dev, device_weights=(name == "c4"))
             ex["ffn_by_config"][name] = ffn_entry(moe, torch, other_wl, 10 if name == "c2" else 3, args.ffn_kernels)
             ex["ffn_by_config"][name]["workload"] = other_wl.describe()
+            bw = backward_entry(moe, torch, workloads, other_wl, 10 if name == "c2" else 3)
+            if bw is not None:
+                ex["backward_by_config"][name] = bw
             del other_wl
             torch.cuda.empty_cache()
         ex.update(decomposition_extras(moe, torch, np, workloads, dev, cpu=not args.no_cpu_baseline))
