@@ -566,6 +566,7 @@ def main():
             torch.cuda.empty_cache()
         ex.update(decomposition_extras(moe, torch, np, workloads, dev, cpu=not args.no_cpu_baseline))
         ex.update(histogram_and_sinkhorn_extras(moe, torch, np, workloads, dev))
+        ex["popularity_jitter_16_ranks"] = jitter_extras(moe, torch, np, workloads, dev)
         if not args.no_cpu_baseline:
             result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r_main, x_sample, sample_rows, offsets_h, W_main, M)
             result["cpu_baseline"]["decomposition_stress"] = ex["decomposition_stress_128x128"].pop("cpu_oracle")
@@ -691,6 +692,33 @@ def decomposition_extras(moe, torch, np, workloads, dev, cpu=True):
                                "bvn_full": {"matrices": nb, "matrices_per_s": nb / tb, "seconds": tb},
                                "sample": "first %d (greedy) / %d (BvN) of the %d stress matrices, OpenMP over matrices" % (ng, nb, B)}
     out["decomposition_stress_128x128"] = entry
+    return out
+
+
+def jitter_extras(moe, torch, np, workloads, dev):
+    """The 16-rank configuration with per-source popularity jitter (every source rank multiplies the expert popularity
+    by its own lognormal(0, 0.5) factors): with one popularity for all sources every matching carries about 1/N of the
+    traffic; with jitter the matchings are as unequal as in the paper's Figure 2."""
+    cfg = workloads.CONFIGS["c2"]
+    out = {}
+    for label, jit in (("shared_popularity", 0.0), ("per_source_jitter_0.5", 0.5)):
+        ids = torch.from_numpy(workloads.config_routing(cfg, per_rank_jitter=jit)).to(dev)
+        traffic, _ = moe.moe_route_histogram(ids, cfg.E)
+        g = moe.moe_decompose_greedy(traffic.unsqueeze(0), cfg.N * 2, zero_diag=True)
+        b = moe.moe_decompose_bvn(traffic.unsqueeze(0), (cfg.N - 1) ** 2 + 1, zero_diag=True)
+        torch.cuda.synchronize()
+        k = int(g["counts"][0].item())
+        A = traffic.clone()
+        A.fill_diagonal_(0)
+        dur = g["durations"][0, :k].cpu().numpy().astype(float)
+        shipped = float(A.sum().item() - g["residual"][0].sum().item())
+        out[label] = {"greedy_matchings_uncapped": k, "greedy_durations": [int(v) for v in dur],
+                      "greedy_first_%d_ship_fraction" % cfg.kmax: None, "bvn_matchings": int(b["counts"][0].item()),
+                      "ideal_all_to_all_rows": int(b["pad_total"][0].item()), "sum_of_greedy_durations": int(dur.sum()),
+                      "off_diagonal_rows": int(A.sum().item()), "shipped_uncapped": shipped}
+        gk = moe.moe_decompose_greedy(traffic.unsqueeze(0), cfg.kmax, zero_diag=True)
+        torch.cuda.synchronize()
+        out[label]["greedy_first_%d_ship_fraction" % cfg.kmax] = 1.0 - float(gk["residual"][0].sum().item()) / float(A.sum().item())
     return out
 
 
