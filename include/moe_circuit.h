@@ -6,8 +6,10 @@
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns every
- *     buffer; the library neither allocates nor frees device memory and keeps no state between
- *     calls except the optional kernel-timing table below.
+ *     buffer; the library neither allocates nor frees device memory.  State kept between calls:
+ *     the optional kernel-timing table, the settings of the test / measurement hooks
+ *     (moe_ffn_tile_override, moe_decompose_profile), per-device facts looked up once (number of
+ *     compute units, kernel attributes) and the fixed work area of moe_slice_table_static.
  *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls validate their arguments
  *     on the host, enqueue their kernels on that stream and return without synchronising.
  *   - Return value: MOE_OK or a negative moe_status.  Nothing throws across this boundary.  On an

@@ -3,15 +3,18 @@
 // decompositions pay, so all slices are issued by launches whose number does not depend on the
 // number of matchings).
 //
-// Two grouped GEMMs on the bf16 MFMA units, each a persistent kernel looping over output tiles:
+// Two grouped GEMMs on the bf16 MFMA units, persistent kernels looping over output tiles (for bf16 weights and 256-row
+// blocks both run in one launch, phase-2 tiles waiting for the rows of H they read):
 //   phase 1:  H = silu(X Wg^T) * (X Wu^T)     tile = BM rows x (128 gate + 128 up) columns
 //   phase 2:  Y = H Wd^T                      tile = BM rows x 256 columns
 // A tile never spans two (slice, expert) groups.  Both operands are K-contiguous, are copied
 // global -> LDS in K slabs (2 to 4 in flight, XOR-swizzled 16-byte chunks; fp8 weights pass through
 // registers to be dequantised) and read back as 16-byte MFMA fragments.  The weights feed the MFMA
 // "A" port so that each lane ends up with 4 consecutive output columns of one row and can store
-// 8 bytes at a time.  bf16 schedules with large groups run ffn_adaptive_kernel, the others (and
-// fp8 weights) the fixed-shape ffn_gemm_kernel.
+// 8 bytes at a time.  bf16 schedules with large groups run the adaptive-shape kernels (ffn_fused_kernel /
+// ffn_adaptive_kernel), the others (and fp8 weights) the fixed-shape ffn_gemm_kernel.
+// moe_expert_ffn_backward_sliced (the backward pass: the exchange of Section 2.1 repeated for the gradients) runs the
+// same adaptive-shape kernels on other operands.
 #include "common.hpp"
 #include <type_traits>
 #include <algorithm>
