@@ -567,6 +567,7 @@ def main():
         ex.update(decomposition_extras(moe, torch, np, workloads, dev, cpu=not args.no_cpu_baseline))
         ex.update(histogram_and_sinkhorn_extras(moe, torch, np, workloads, dev))
         ex["popularity_jitter_16_ranks"] = jitter_extras(moe, torch, np, workloads, dev)
+        ex["fragmentation_16_ranks"] = fragmentation_extras(moe, torch, np, workloads, dev)
         if not args.no_cpu_baseline:
             result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r_main, x_sample, sample_rows, offsets_h, W_main, M)
             result["cpu_baseline"]["decomposition_stress"] = ex["decomposition_stress_128x128"].pop("cpu_oracle")
@@ -692,6 +693,46 @@ def decomposition_extras(moe, torch, np, workloads, dev, cpu=True):
                                "bvn_full": {"matrices": nb, "matrices_per_s": nb / tb, "seconds": tb},
                                "sample": "first %d (greedy) / %d (BvN) of the %d stress matrices, OpenMP over matrices" % (ng, nb, B)}
     out["decomposition_stress_128x128"] = entry
+    return out
+
+
+def fragmentation_extras(moe, torch, np, workloads, dev):
+    """The paper's point about fragmentation, measured on real kernels (Sections 3.1, 5): the 16-rank configuration's FFN
+    on the hottest rank under the greedy schedule (8 matchings + rest: 10 slices), under the full BvN schedule (224
+    matchings: 226 slices of a few dozen rows per expert) and unsliced (all rows of an expert in one group)."""
+    cfg = workloads.CONFIGS["c2"]
+    wl = Workload(moe, torch, np, workloads, cfg, dev)
+    wl.step()
+    torch.cuda.synchronize()
+    out = {}
+
+    def timed(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e6
+
+    out["greedy_schedule"] = {"slices": wl.S, "ffn_us": timed(wl.ffn)}
+    kb = wl.kb
+    off_b = moe.moe_slice_table(wl.ids, cfg.E, wl.r, wl.traffic, wl.b_out["perms"][0], wl.b_out["durations"][0], wl.b_out["counts"], kb)
+    torch.cuda.synchronize()
+    assert int(off_b[-1].item()) == wl.M
+    sizes = (off_b[1:] - off_b[:-1]).float()
+    out["bvn_schedule"] = {"slices": kb + 2, "matchings": int(wl.b_out["counts"][0].item()),
+                           "mean_rows_per_nonempty_group": float(sizes[sizes > 0].mean().item()),
+                           "ffn_us": timed(lambda: moe.moe_expert_ffn_sliced(wl.x, off_b, kb + 2, cfg.E_loc, y=wl.y, workspace=wl.ffn_ws, **wl.w))}
+    # unsliced: the same rows regrouped by expert only (what an all-to-all that delivers everything at once would hand over)
+    off_g = wl.offsets.cpu().numpy().astype(np.int64)
+    per_expert = np.zeros(cfg.E_loc, dtype=np.int64)
+    for g in range(len(off_g) - 1):
+        per_expert[g % cfg.E_loc] += off_g[g + 1] - off_g[g]
+    off_u = torch.from_numpy(np.concatenate([[0], np.cumsum(per_expert)]).astype(np.int32)).to(dev)
+    out["unsliced"] = {"slices": 1, "ffn_us": timed(lambda: moe.moe_expert_ffn_sliced(wl.x, off_u, 1, cfg.E_loc, y=wl.y, workspace=wl.ffn_ws, **wl.w))}
+    for k in out:
+        out[k]["tflops"] = 6.0 * cfg.d * cfg.f * wl.M / out[k]["ffn_us"] / 1e6
     return out
 
 
