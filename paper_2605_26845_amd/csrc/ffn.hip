@@ -568,25 +568,26 @@ void ffn_gemm_kernel(FfnArgs a) {
 // the MFMAs queued behind a copy waiting) for a fifth of the time.
 // The barrier at the end of slab s publishes slab s + 1 and frees the buffer of slab s; the copies of slab s + NSS
 // go out from there on, spaced between the MFMAs (slot 0 = rest of slab s, slot i = K step i - 1 of slab s + 1).
+constexpr int NW = 8;                                         // wavefronts per workgroup
 template <int CLS> struct Cls {
     static_assert(CLS == 0 || CLS == 1, "two shape classes");
-    static constexpr int WMW = CLS == 0 ? 4 : 2, WNW = 8 / WMW;
-    static constexpr int MB = 2, NQ = 4;                                    // 32-row / 32-column blocks per wavefront
+    static constexpr int WMW = (CLS == 0 ? 4 : 2) * NW / 8, WNW = NW / WMW;
+    static constexpr int MB = 16 / NW, NQ = 4;                                    // 32-row / 32-column blocks per wavefront
     static constexpr int BMc = 32 * MB * WMW, BNc = 32 * NQ * WNW;
     static constexpr int U = BNc / 256;                                     // column units per tile
     static constexpr int ROWB = CLS == 0 ? 128 : 64;                        // bytes per slab row
     static constexpr int SUB = ROWB / 32;                                   // MFMA K steps (of 16) per slab
-    static constexpr int RPC = 8192 / ROWB;                                 // slab rows one copy of the workgroup deposits
+    static constexpr int RPC = NW * 1024 / ROWB;                                 // slab rows one copy of the workgroup deposits
     static constexpr int A_BYTES = BMc * ROWB, B_BYTES = BNc * ROWB, SLAB = A_BYTES + B_BYTES;
     static constexpr int NSS = CLS == 1 ? 3 : 2;                            // slabs resident in LDS
     static constexpr int CA = BMc / RPC, CB = BNc / RPC, NCOPY = CA + CB;   // copies per wavefront and slab
     // copies per slot (slot 0, 1, 2; none later)
-    static constexpr int S0 = CLS == 0 ? 4 : 3, S1 = CLS == 0 ? 4 : 2, S2 = 0;
+    static constexpr int S0 = (CLS == 0 ? 4 : 3) * 8 / NW, S1 = NCOPY - S0, S2 = 0;
     static_assert(S0 + S1 + S2 == NCOPY && (S2 == 0 || SUB > 2) && (S1 == 0 || SUB > 1), "the slots hold every copy and end before the next slab's last K step");
 };
 constexpr int STAGE_OFF = 131072;                             // slab buffers below (2 x 64 KiB >= 3 x 40 KiB), output staging above
 constexpr int STAGE_WAVE = 4096;                              // staging per wavefront: 32 rows x 128 bytes
-constexpr int ADAPTIVE_LDS = STAGE_OFF + 8 * STAGE_WAVE;      // 160 KiB: all of a compute unit's LDS
+constexpr int ADAPTIVE_LDS = STAGE_OFF + NW * STAGE_WAVE;      // 160 KiB: all of a compute unit's LDS
 
 // GATHER (phase 1 with a row map): the rows of a tile lie anywhere in x, so every thread carries the 64-bit address of
 // its rows; otherwise the rows of a tile are consecutive and one buffer descriptor per tile (64-bit base at the
@@ -699,7 +700,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
     //      are fixed for a tile, so a copy costs no vector ALU work.  Rows past the end of the block re-read its last row.
     const __bf16* Abase = (PHASE == 1 ? a.x : a.g2.A);
     unsigned long long aB = 0;                         // address of the tile's first row of the A operand (plain rows)
-    const unsigned char* a_ptr[GATHER ? 4 : 1];        // address of this thread's chunk of each of its rows (gathered rows)
+    const unsigned char* a_ptr[GATHER ? 32 / NW : 1];        // address of this thread's chunk of each of its rows (gathered rows)
     // B rows come from w_gate / w_up (phase 1) or w_down (phase 2) of the tile's expert: base address of the first and
     // distance to the second.  (One variable per quantity, set once per tile: a choice between variables inside the
     // unrolled copy code would keep them in memory.)
@@ -707,7 +708,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
     unsigned int b_voff = 0;
     bool counted_stores = false;                       // the previous tile's output went out as a known number of stores
     int m0 = 0, m_end = 0, nt = 0;
-    unsigned int a_voff[4];
+    unsigned int a_voff[32 / NW];
     unsigned int b_soff[8];
 
     auto setup = [&](auto tag, int nt_) __attribute__((always_inline)) {
@@ -762,10 +763,10 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
         if (n < C::CA) {
             if constexpr (GATHER) {
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_ptr[n] + koff),
-                                                 (__attribute__((address_space(3))) void*)(base + n * 8192), 16, 0, 0);
+                                                 (__attribute__((address_space(3))) void*)(base + n * (NW * 1024)), 16, 0, 0);
             } else {
                 const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void*)aB, 0, 0xFFFFFFFF, 0x00020000);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * 8192), 16,
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (__attribute__((address_space(3))) void*)(base + n * (NW * 1024)), 16,
                                                          a_voff[n], koff, 0, FUSED && PHASE == 2 ? DEVICE_SCOPE : 0);
             }
         } else {
@@ -773,7 +774,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
             const unsigned long long up = (j / CPSTRIP) & 1;
             const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc((void*)(wB + up * wB_up), 0, 0xFFFFFFFF, 0x00020000);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB,
-                                                     (__attribute__((address_space(3))) void*)(base + C::A_BYTES + j * 8192), 16,
+                                                     (__attribute__((address_space(3))) void*)(base + C::A_BYTES + j * (NW * 1024)), 16,
                                                      b_voff, b_soff[j] + koff, 0, 0);
         }
     };
@@ -803,7 +804,8 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
         constexpr int ROWB = C::ROWB, NMF = MB * NQ, NR = MB + NQ;
         constexpr int LPS = C::NCOPY;                                   // copies every wavefront issues per slab
         constexpr int NSTORE = MB * (PHASE == 1 ? 4 : 8) * (EPI == 1 ? 3 : 1);      // 1 KiB stores per wavefront and tile
-        static_assert((NSS - 1) * C::NCOPY + NSTORE < 64 && NSS * C::SLAB <= STAGE_OFF, "pipeline shape");
+        constexpr bool COUNTABLE = (NSS - 1) * C::NCOPY + NSTORE < 64;     // (the counter of memory operations in flight has 6 bits)
+        static_assert((NSS - 1) * C::NCOPY < 64 && NSS * C::SLAB <= STAGE_OFF, "pipeline shape");
         static_assert(Cls<0>::MB == Cls<1>::MB, "a tile of either class issues NSTORE output stores");
         const int NS = K / (ROWB / 2);
         const int wm = wave / C::WNW, wn = wave % C::WNW;
@@ -835,7 +837,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
 
         // Issued so far, oldest first: slab 0, the slabs of the other buffers, the previous tile's output stores.  The
         // stores need not be awaited when their number is known (memory operations of a wavefront are counted in order).
-        if (counted_stores) wait_vmcnt<(NSS - 1) * LPS + NSTORE>(); else wait_vmcnt<(NSS - 1) * LPS>();
+        if (COUNTABLE && counted_stores) wait_vmcnt<COUNTABLE ? (NSS - 1) * LPS + NSTORE : 0>(); else wait_vmcnt<(NSS - 1) * LPS>();
         lds_barrier();                   // slab 0 is in LDS
         if (FUSED && PHASE == 1) signal_ready(1);
         // Ticket of the next tile: the counter's old value returns while slab 0 is multiplied and is turned into a
@@ -993,6 +995,8 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
                 }
                 // backward pass: the gradient of the hidden activations at this lane's 2 x 4 groups of 4 columns (rows
                 // and units past the end read the last valid ones; what is computed from them is not stored)
+                // backward pass: the gradient of the hidden activations at this lane's 2 x 4 groups of 4 columns (rows
+                // and units past the end read the last valid ones; what is computed from them is not stored)
                 u32x2 dhv[EPI == 1 ? 8 : 1];
                 if constexpr (EPI == 1) {
                     const int row_c = min(wrow + mb * 32 + el31, em_end - 1);
@@ -1001,7 +1005,10 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
                     for (int c = 0; c < 8; ++c) dhv[c] = *reinterpret_cast<const u32x2*>(src + c * 8);
                 }
 #pragma unroll
-                for (int pass = 0; pass < NPASS; ++pass) {
+                for (int step = 0; step < NPASS; ++step) {
+                // backward pass: h goes out first; the same sweep leaves dg and du in the accumulators of g and u, from
+                // where the two later sweeps store them (one exponential per element)
+                const int pass = EPI == 1 ? (step + 2) % 3 : 0;
 #pragma unroll
                 for (int hq = 0; hq < NH; ++hq) {
 #pragma unroll
@@ -1010,14 +1017,19 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
                         for (int vg = 0; vg < 4; ++vg) {
                             float hv[4];
                             if constexpr (EPI == 1) {
-                                const bf16x4 d4 = __builtin_bit_cast(bf16x4, dhv[q * 4 + vg]);
+                                if (step == 0) {
+                                    const bf16x4 d4 = __builtin_bit_cast(bf16x4, dhv[q * 4 + vg]);
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) {
-                                    const float g = acc[mb][q][vg * 4 + j], u = acc[mb][q + 2][vg * 4 + j], dh = (float)d4[j];
-                                    const float sig = __builtin_amdgcn_rcpf(1.0f + __expf(-g));
-                                    hv[j] = pass == 0 ? dh * u * (sig * (1.0f + g * (1.0f - sig)))       // dg = dh * u * silu'(g)
-                                          : pass == 1 ? dh * (g * sig)                                    // du = dh * silu(g)
-                                                      : (g * sig) * u;                                    // h
+                                    for (int j = 0; j < 4; ++j) {
+                                        const float g = acc[mb][q][vg * 4 + j], u = acc[mb][q + 2][vg * 4 + j], dh = (float)d4[j];
+                                        const float sig = __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+                                        hv[j] = (g * sig) * u;                                                  // h
+                                        acc[mb][q][vg * 4 + j] = dh * u * (sig * (1.0f + g * (1.0f - sig)));    // dg = dh * u * silu'(g)
+                                        acc[mb][q + 2][vg * 4 + j] = dh * (g * sig);                            // du = dh * silu(g)
+                                    }
+                                } else {
+#pragma unroll
+                                    for (int j = 0; j < 4; ++j) hv[j] = acc[mb][step == 1 ? q : q + 2][vg * 4 + j];
                                 }
                             } else {
 #pragma unroll
@@ -1069,7 +1081,7 @@ __device__ __forceinline__ void ffn_adaptive_body(const FfnArgs& a, unsigned cha
 }
 
 template <int PHASE, bool GATHER, int EPI = 0>
-__global__ __launch_bounds__(512, 1)
+__global__ __launch_bounds__(NW * 64, 1)
 void ffn_adaptive_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     ffn_adaptive_body<PHASE, GATHER, false, EPI>(a, smem);
@@ -1080,7 +1092,7 @@ void ffn_adaptive_kernel(FfnArgs a) {
 // acquire by the reader, at device scope).  The tail of phase 1 is filled with phase-2 tiles, and a call costs one
 // launch of the matrix kernels whatever the number of slices.
 template <bool GATHER>
-__global__ __launch_bounds__(512, 1)
+__global__ __launch_bounds__(NW * 64, 1)
 void ffn_fused_kernel(FfnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     ffn_adaptive_body<1, GATHER, true>(a, smem);
@@ -1176,7 +1188,7 @@ moe_status launch_adaptive(const FfnArgs& a, long long max_tiles, hipStream_t s,
     const long long slots = num_cus();
     const int grid = (int)(max_tiles < slots ? max_tiles : slots);
     moe::LaunchScope k(name ? name : (PHASE == 1 ? "ffn_gemm1_kernel" : "ffn_gemm2_kernel"), s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ADAPTIVE_LDS, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), ADAPTIVE_LDS, s, a);
     return k.done();
 }
 
@@ -1193,7 +1205,7 @@ moe_status launch_fused(const FfnArgs& a, long long max_tiles, hipStream_t s) {
     const long long slots = num_cus();
     const int grid = (int)(max_tiles < slots ? max_tiles : slots);
     moe::LaunchScope k("ffn_fused_kernel", s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ADAPTIVE_LDS, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), ADAPTIVE_LDS, s, a);
     return k.done();
 }
 
