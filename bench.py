@@ -542,6 +542,8 @@ def main():
         ex["ffn_by_config"] = {cfg.name: ffn_figures(cfg, M, wl.S, gemm_us, other_us)}
         ex["ffn_by_config"][cfg.name]["one_launch_per_phase"] = result["ffn_one_launch_per_phase"]
         ex["vendor_gemm_same_shape"] = vendor_gemm(torch, wl)
+        ex["mfma_only_probe"] = mfma_probe(moe, torch)
+        roofline["measured_mfma_only_tflops"] = ex["mfma_only_probe"]["ffn_like_operands"]["tflops"]
         ex["backward_by_config"] = {cfg.name: backward_entry(moe, torch, workloads, wl, 3)}
         ex.update(ffn_granularity(moe, torch, np, wl))
         ex["makespan_model_us"] = makespan_extras(moe, np, cfg, wl.traffic, wl.g_out, wl.b_out, ex["expert_time_us_vs_rows"])
@@ -606,6 +608,22 @@ def vendor_gemm(torch, wl):
     flops = 2.0 * wl.M * w.shape[0] * wl.cfg.d
     return {"shape": "[%d x %d] x [%d x %d]^T, bf16" % (wl.M, wl.cfg.d, w.shape[0], wl.cfg.d), "us": us, "tflops": flops / us / 1e6,
             "frac_mfma_peak": flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS}
+
+
+def mfma_probe(moe, torch):
+    """The FFN's MFMA instruction issued from registers alone on every SIMD of the chip (no operand moves): the rate
+    the matrix cores sustain at the clock the power limit allows, on operands drawn like the FFN's and on zeros."""
+    out = {}
+    wgs, iters = 256, 100000
+    sink = torch.empty((wgs * 256,), dtype=torch.float32, device="cuda")
+    flop = wgs * 4.0 * iters * 16 * 32768
+    for key, data in (("ffn_like_operands", 1), ("zero_operands", 0)):
+        moe.moe_probe_mfma_bf16(data, iters // 10, wgs, sink)
+        times, _ = kernel_times(moe, torch, lambda: moe.moe_probe_mfma_bf16(data, iters, wgs, sink), 2)
+        us = times["mfma_probe_kernel"]
+        out[key] = {"us": us, "tflops": flop / us / 1e6, "frac_mfma_peak": flop / us / 1e6 / MFMA_BF16_PEAK_TFLOPS}
+    out["what"] = "v_mfma_f32_32x32x16_bf16 from registers, 4 wavefronts on each of 256 compute units, %d instructions per wavefront" % (16 * iters)
+    return out
 
 
 def decomposition_extras(moe, torch, np, workloads, dev, cpu=True):

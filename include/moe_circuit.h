@@ -363,6 +363,22 @@ moe_status moe_order_matchings(const int32_t* traffic, int N, const uint8_t* per
                                const moe_cost_model* cost, int32_t* order_out);
 
 /* ---------------------------------------------------------------------------------------------
+ * moe_probe_mfma_bf16 -- measurement aid, not meant for production callers: the rate the matrix
+ * cores sustain on v_mfma_f32_32x32x16_bf16 (the instruction of the expert FFN) from registers
+ * alone, i.e. the ceiling of a bf16 contraction on this chip at the clock its power limit allows.
+ * Enqueues one kernel of `workgroups` workgroups of four wavefronts; every wavefront issues
+ * 16 * iters instructions of 32768 flop each, so the launch performs
+ * workgroups * 4 * iters * 16 * 32768 flop; time it with the kernel timing below
+ * ("mfma_probe_kernel") or with events of the caller.
+ *   data        0 = all operands zero, 1 = operands drawn like the FFN's (about N(0,1) times
+ *               N(0,0.02)); the sustained clock depends on it
+ *   iters       1 .. 2^22
+ *   workgroups  1 .. 4096 (one per compute unit fills the chip)
+ *   sink        out  float [workgroups * 256]  one accumulator per thread (keeps the loop alive)
+ * ------------------------------------------------------------------------------------------- */
+moe_status moe_probe_mfma_bf16(int data, int iters, int workgroups, float* sink, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Kernel timing (measurement aid).  While enabled, every kernel launch of this library is
  * bracketed by HIP events on the caller's stream.  moe_kernel_timing_read synchronises those
  * events, adds them up per kernel name and resets the table.

@@ -32,7 +32,7 @@ EXPORTS = [
     "moe_kernel_timing_read", "moe_kernel_timing_select", "moe_last_hip_error", "moe_makespan_model", "moe_order_matchings", "moe_decompose_sinkhorn_bvn", "moe_slice_table_rows_workspace_bytes",
     "moe_slice_table_rows", "moe_expert_ffn_sliced_mapped", "moe_ffn_tile_override",
     "moe_slice_table_static", "moe_decompose_profile", "moe_combine_topk_sum",
-    "moe_ffn_backward_workspace_bytes", "moe_expert_ffn_backward_sliced",
+    "moe_ffn_backward_workspace_bytes", "moe_expert_ffn_backward_sliced", "moe_probe_mfma_bf16",
 ]
 
 _lib = None
@@ -114,6 +114,8 @@ def load():
     L.moe_expert_ffn_backward_sliced.restype = ci
     L.moe_combine_topk_sum.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     L.moe_combine_topk_sum.restype = ci
+    L.moe_probe_mfma_bf16.argtypes = [ci, ci, ci, vp, vp]
+    L.moe_probe_mfma_bf16.restype = ci
     L.moe_ffn_tile_override.argtypes = [ci, ci, ci]
     L.moe_ffn_tile_override.restype = ci
     L.moe_kernel_timing_enable.argtypes = [ci]
@@ -411,6 +413,19 @@ def moe_combine_topk_sum(y, row_of, gate=None, out=None):
     _check(load().moe_combine_topk_sum(_ptr(y), _ptr(row_of), _ptr(gate), T, topk, d, R, _ptr(out), _stream()),
            "moe_combine_topk_sum")
     return out
+
+
+def moe_probe_mfma_bf16(data: int, iters: int, workgroups: int, sink=None):
+    """Measurement aid: one launch of the register-only MFMA loop (workgroups * 4 * iters * 16 * 32768 flop); returns
+    the sink tensor (float32 [workgroups * 256])."""
+    import torch
+    if sink is None:
+        sink = torch.empty((int(workgroups) * 256,), dtype=torch.float32, device="cuda")
+    _dev_check(sink, torch.float32, "sink")
+    if sink.numel() < int(workgroups) * 256:
+        raise MoeError("sink must hold workgroups * 256 floats")
+    _check(load().moe_probe_mfma_bf16(int(data), int(iters), int(workgroups), _ptr(sink), _stream()), "moe_probe_mfma_bf16")
+    return sink
 
 
 def moe_ffn_tile_override(tile_rows: int = 0, kernels: int = 0, panel_groups: int = 0):

@@ -63,6 +63,15 @@ def test_host_side_argument_checks_need_no_gpu():
     assert L.moe_kernel_timing_read(None, None, None, 0) == 0
 
 
+def test_probe_argument_checks_need_no_gpu():
+    L = moe.load()
+    sink = ctypes.c_void_p(4096)
+    assert L.moe_probe_mfma_bf16(2, 10, 1, sink, None) == -1          # data is 0 or 1
+    assert L.moe_probe_mfma_bf16(1, 0, 1, sink, None) == -1           # at least one iteration
+    assert L.moe_probe_mfma_bf16(1, 10, 5000, sink, None) == -1       # at most 4096 workgroups
+    assert L.moe_probe_mfma_bf16(1, 10, 1, None, None) == -1          # the sink is required
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(moe, "_lib", None)
     monkeypatch.setattr(moe, "_LIB_PATH", str(tmp_path / "nope.so"))

@@ -208,6 +208,25 @@ def test_decompose_profile_hook(lib):
     assert torch.equal(before, prof)
 
 
+def test_mfma_probe(lib):
+    """The measurement kernel runs, is timed under its name, and its accumulators hold what the loop defines: zero for
+    zero operands; with varied operands every accumulator is the same product block added once per iteration, so
+    twice the iterations give twice the value (up to fp32 rounding of the running sums)."""
+    say("mfma probe")
+    z = lib.moe_probe_mfma_bf16(0, 7, 3)
+    torch.cuda.synchronize()
+    assert z.shape == (3 * 256,) and bool((z == 0).all())
+    lib.moe_kernel_timing_enable(True)
+    a = lib.moe_probe_mfma_bf16(1, 8, 2).clone()
+    b = lib.moe_probe_mfma_bf16(1, 16, 2).clone()
+    torch.cuda.synchronize()
+    lib.moe_kernel_timing_enable(False)
+    kt = lib.moe_kernel_timing_read()
+    assert kt["mfma_probe_kernel"][1] == 2 and kt["mfma_probe_kernel"][0] > 0
+    assert bool(torch.isfinite(a).all()) and bool((a != 0).any())
+    assert torch.allclose(b, 2 * a, rtol=1e-3, atol=1e-6)
+
+
 def test_decompose_stress_matrices_128(lib):
     """The batched stress workload at its real shape (128 x 128, Zipf rows), a sample of matrices."""
     say("decompose stress 128")
