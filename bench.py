@@ -40,6 +40,8 @@ def parse():
                          "1 = fixed-shape kernels, 2 = adaptive-shape kernels with one launch per phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="with --no-extras: still run torch.matmul on the phase-1 shape (so that a profiler run holds the vendor kernel)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (reference reading for HBM byte counters)")
     ap.add_argument("--summarize-counters", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
@@ -77,6 +79,8 @@ def kernel_key(name):
         return "ffn_fused_kernel"
     if "copyBuffer" in name:
         return "copy"
+    if name.startswith("Cijk_") or name.startswith("Custom_Cijk_"):
+        return "vendor_gemm"
     for k in ("bvn_kernel", "greedy_kernel", "st_count_kernel", "st_scan_kernel", "ffn_plan_kernel", "hist_kernel", "ffn_expand_fp8_kernel"):
         if k in name:
             return k
@@ -220,22 +224,24 @@ def summarize_mfma(args, counter_csv):
     dur = collections.defaultdict(dict)
     for row in csv.DictReader(open(counter_csv)):
         key = kernel_key(row["Kernel_Name"])
-        if key in FFN_KERNELS:
+        if key in FFN_KERNELS or key == "vendor_gemm":
             acc[key][row["Counter_Name"]].append(float(row["Counter_Value"]))
             dur[key][row["Dispatch_Id"]] = float(row["End_Timestamp"]) - float(row["Start_Timestamp"])
     cfg, M = workload_shape(workload)
     rel = os.path.relpath(os.path.abspath(counter_csv), ROOT)
     lines = ["# MFMA utilisation counters (rocprofv3 --pmc), bench.py workload %s, the FFN matrix kernels" % workload, "",
              "Commands (run from the repository root with TMPDIR=/tmp on the MI355X box; then the summary, no GPU needed):", "",
-             "    rocprofv3 --kernel-trace --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s%s --steps 10 --warmup 2 --no-extras --no-cpu-baseline"
+             "    rocprofv3 --kernel-trace --pmc %s --output-format csv -d %s -o p -- python3 bench.py --workload %s%s --steps 10 --warmup 2 --no-extras --no-cpu-baseline --vendor-gemm"
              % (" ".join(MFMA_COUNTERS), os.path.dirname(rel), workload, bench_flags(args)),
              "    python3 bench.py --workload %s%s --summarize-mfma %s" % (workload, bench_flags(args), rel), "",
-             "(the run also holds bench.py's pass with one launch per FFN phase: the phase kernels below come from that pass)", "",
+             "(the run also holds bench.py's pass with one launch per FFN phase: the phase kernels below come from that pass; vendor_gemm is",
+             "torch.matmul on the shape and data of phase 1, x [M][d] times one expert's gate and up weights [2f][d]^T, the same flop as",
+             "ffn_gemm1_kernel when the rank holds one expert)", "",
              "Averages per dispatch, as the profiler reports them: SQ_* counters are sums over the chip (SQ_VALU_MFMA_BUSY_CYCLES over its 1024 SIMDs,",
              "SQ_BUSY_CU_CYCLES over its 256 compute units, SQ_WAVE_CYCLES / SQ_WAIT_ANY over all wavefronts), GRBM_GUI_ACTIVE is the sum of the busy",
              "shader-clock cycles of the 8 accelerator dies (so cycles per launch = GRBM_GUI_ACTIVE / 8).", ""]
     names = sorted({c for k in acc for c in acc[k]})
-    kernels = [k for k in FFN_KERNELS if k in acc]
+    kernels = [k for k in FFN_KERNELS + ("vendor_gemm",) if k in acc]
     lines += ["| counter | " + " | ".join(kernels) + " |", "|---|" + "---|" * len(kernels)]
     mean = {k: {c: sum(v) / len(v) for c, v in acc[k].items()} for k in kernels}
     for c in names:
@@ -244,6 +250,7 @@ def summarize_mfma(args, counter_csv):
     lines.append("| average duration under the profiler, us | " + " | ".join("%.1f" % (sum(dur[k].values()) / len(dur[k]) / 1e3) for k in kernels) + " |")
     lines.append("")
     flops = {k: v["flop"] for k, v in ffn_kernel_work(cfg, M).items()}
+    flops["vendor_gemm"] = 4.0 * cfg.d * cfg.f * M
     peak_per_cycle = MFMA_BF16_PEAK_TFLOPS * 1e12 / (SHADER_CLOCK_GHZ * 1e9)
     for k in kernels:
         m = mean[k]
@@ -573,7 +580,9 @@ def main():
         if not args.no_cpu_baseline:
             result["cpu_baseline"] = cpu_baseline(cfg, ids_h, r_main, x_sample, sample_rows, offsets_h, W_main, M)
             result["cpu_baseline"]["decomposition_stress"] = ex["decomposition_stress_128x128"].pop("cpu_oracle")
-    elif not args.no_cpu_baseline:
+    elif args.vendor_gemm:
+        result["vendor_gemm_same_shape"] = vendor_gemm(torch, wl)
+    if args.no_extras and not args.no_cpu_baseline:
         sample_rows = np.unique(np.linspace(0, M - 1, num=min(M, cpu_sample_rows(cfg)), dtype=np.int64))
         x_sample = wl.x[torch.from_numpy(sample_rows).to(dev)].view(torch.int16).cpu().numpy().view(np.uint16)
         result["cpu_baseline"] = cpu_baseline(cfg, wl.ids_h, wl.r, x_sample, sample_rows, wl.offsets.cpu().numpy(), wl.W, M)
