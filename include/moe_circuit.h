@@ -300,8 +300,9 @@ moe_status moe_combine_topk_sum(const void* y, const int32_t* row_of, const floa
  * moe_ffn_tile_override -- test and measurement hook, not meant for production callers.  The FFN
  * calls choose the height of their row blocks (64, 128 or 256 rows), the kernel family (one
  * whose tile shape adapts to ragged group ends, or fixed-shape tiles) and the order in which the
- * output tiles are walked from the shape of the schedule; this call pins any of these choices for all following moe_expert_ffn_sliced(_mapped) calls of
- * the process, so that every kernel can be driven on small inputs and timed on any input.
+ * output tiles are walked from the shape of the schedule; this call pins any of these choices for
+ * all following moe_expert_ffn_sliced(_mapped) calls of the process, so that every kernel can be
+ * driven on small inputs and timed on any input.
  *   tile_rows    0 = chosen per call (the default), else 64, 128 or 256
  *   kernels      0 = chosen per call (the default), 1 = always the fixed-shape kernels, 2 = the
  *                adaptive-shape kernels with one launch per phase instead of both phases in one
