@@ -391,6 +391,46 @@ def ffn_kernel_us(times):
     return gemm, other
 
 
+def graph_replay_step(moe, torch, wl, reps):
+    """The whole step recorded once into a HIP graph (the library makes no runtime call but kernel launches, so the
+    capture holds the histogram, both decompositions -- BvN on a forked branch --, the slice table and the FFN) and
+    replayed: what the launches and the gaps between them cost the eager step.  Wall time per replay; errors are reported,
+    not raised (a measurement beside the headline, not part of it)."""
+    c = wl.cfg
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cur = torch.cuda.current_stream()
+            moe.moe_route_histogram(wl.ids, c.E, traffic=wl.traffic, expert_counts=wl.counts)
+            wl.side.wait_stream(cur)
+            with torch.cuda.stream(wl.side):
+                moe.moe_decompose_bvn(wl.traffic.unsqueeze(0), wl.kb, zero_diag=True, out=wl.b_out)
+            moe.moe_decompose_greedy(wl.traffic.unsqueeze(0), c.kmax, zero_diag=True, out=wl.g_out)
+            moe.moe_slice_table(wl.ids, c.E, wl.r, wl.traffic, wl.g_out["perms"][0], wl.g_out["durations"][0],
+                                wl.g_out["counts"], c.kmax, offsets=wl.offsets, workspace=wl.st_ws)
+            wl.ffn()
+            cur.wait_stream(wl.side)
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / reps * 1e6
+        wl.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            wl.step()
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t0) / reps * 1e6
+        return {"replay_us": us, "eager_us": eager_us, "tflops_replay": 6.0 * c.d * c.f * wl.M / us / 1e6}
+    except Exception as exc:                                              # noqa: BLE001
+        torch.cuda.synchronize()
+        return {"error": str(exc)[:200]}
+
+
 def ffn_entry(moe, torch, wl, reps, kernels):
     """FFN figures of one workload: inside the whole step (the decompositions run before and beside the FFN, as in the
     timed region), with the FFN call issued back to back (the chip then never idles between two calls and settles at a
@@ -549,6 +589,7 @@ def main():
         ex["ffn_by_config"] = {cfg.name: ffn_figures(cfg, M, wl.S, gemm_us, other_us)}
         ex["ffn_by_config"][cfg.name]["one_launch_per_phase"] = result["ffn_one_launch_per_phase"]
         ex["vendor_gemm_same_shape"] = vendor_gemm(torch, wl)
+        ex["step_as_hip_graph"] = {cfg.name: graph_replay_step(moe, torch, wl, 10)}
         ex["mfma_only_probe"] = mfma_probe(moe, torch)
         roofline["measured_mfma_only_tflops"] = ex["mfma_only_probe"]["ffn_like_operands"]["tflops"]
         ex["backward_by_config"] = {cfg.name: backward_entry(moe, torch, workloads, wl, 3)}
@@ -568,6 +609,8 @@ def main():
             other_wl = Workload(moe, torch, np, workloads, workloads.CONFIGS[name], dev, device_weights=(name == "c4"))
             ex["ffn_by_config"][name] = ffn_entry(moe, torch, other_wl, 10 if name == "c2" else 3, args.ffn_kernels)
             ex["ffn_by_config"][name]["workload"] = other_wl.describe()
+            if name == "c2":
+                ex["step_as_hip_graph"][name] = graph_replay_step(moe, torch, other_wl, 30)
             bw = backward_entry(moe, torch, workloads, other_wl, 10 if name == "c2" else 3)
             if bw is not None:
                 ex["backward_by_config"][name] = bw

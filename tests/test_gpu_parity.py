@@ -967,6 +967,69 @@ def config_weights(cfg):
     return _WEIGHTS[cfg.name]
 
 
+def test_whole_path_under_graph_capture(lib):
+    """The library allocates nothing, copies nothing and clears nothing with runtime calls, so histogram -> greedy ->
+    slice table (on the built-in work area) -> FFN can be recorded into a HIP graph once, with the row capacity as M
+    (rows past offsets[last] are left alone), and replayed on new routings and activations.  Every replay is compared
+    bit for bit with the same calls made eagerly on the same inputs (eager work and synchronisation between replays)."""
+    say("whole path under graph capture")
+    cfg = workloads.CONFIGS["tiny"]
+    N, E, kmax, r = cfg.N, cfg.E, cfg.kmax, 3
+    cap = N * cfg.T * cfg.topk                                         # no routing sends more rows than this to one rank
+    W, Wd = config_weights(cfg)
+    ids_s = torch.zeros((N, cfg.T, cfg.topk), dtype=torch.int32, device=DEV)
+    x_s = torch.zeros((cap, cfg.d), dtype=torch.bfloat16, device=DEV)
+    y_s = torch.zeros((cap, cfg.d), dtype=torch.bfloat16, device=DEV)
+    traffic = torch.zeros((N, N), dtype=torch.int32, device=DEV)
+    counts_e = torch.zeros((N, E), dtype=torch.int32, device=DEV)
+    sched = dict(perms=torch.zeros((1, kmax, N), dtype=torch.uint8, device=DEV), durations=torch.zeros((1, kmax), dtype=torch.int32, device=DEV),
+                 counts=torch.zeros((1,), dtype=torch.int32, device=DEV), residual=torch.zeros((1, N, N), dtype=torch.int32, device=DEV), hashes=None)
+    offsets = torch.zeros(((kmax + 2) * cfg.E_loc + 1,), dtype=torch.int32, device=DEV)
+    ws = torch.empty((lib.moe_ffn_workspace_bytes(cap, cfg.d, cfg.f),), dtype=torch.uint8, device=DEV)
+
+    def path():
+        lib.moe_route_histogram(ids_s, E, traffic=traffic, expert_counts=counts_e)
+        lib.moe_decompose_greedy(traffic.view(1, N, N), kmax, zero_diag=True, out=sched)
+        lib.moe_slice_table_static(ids_s, E, r, traffic, sched["perms"][0], sched["durations"][0], sched["counts"], kmax, offsets)
+        lib.moe_expert_ffn_sliced(x_s, offsets, kmax + 2, cfg.E_loc, y=y_s, workspace=ws, **Wd)
+
+    def load_inputs(seed):
+        rng = np.random.default_rng(seed)
+        ids_s.copy_(torch.from_numpy(rng.integers(0, E, size=(N, cfg.T, cfg.topk), dtype=np.int32)))
+        x_s.copy_(workloads.activations_on_device(cap, cfg.d, 100 + seed, DEV))
+
+    def clear():
+        for t in (traffic, sched["perms"], sched["durations"], sched["counts"], sched["residual"], offsets):
+            t.zero_()
+        y_s.fill_(0.5)
+
+    outputs = lambda: [t.clone() for t in (traffic, sched["perms"], sched["durations"], sched["counts"], sched["residual"], offsets, y_s)]
+    load_inputs(0)
+    path()                                                             # warm-up outside the capture (per-device kernel attributes)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for seed in (1, 2, 3):
+        load_inputs(seed)
+        clear()
+        path()
+        torch.cuda.synchronize()
+        eager = outputs()
+        clear()                                                         # (entries past counts / offsets[last] are left alone by the calls)
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("traffic", "perms", "durations", "counts", "residual", "offsets", "y"), eager, outputs()):
+            assert torch.equal(a, b), (seed, name)
+        M = int(offsets[-1].item())
+        assert 0 < M < cap and bool((y_s[M:] == 0.5).all())                 # rows past the schedule are untouched
+    # one replay against the oracle as well (the eager path is what the other tests compare with it)
+    off = offsets.cpu().numpy().astype(np.int64)
+    rows = np.arange(int(off[-1]), dtype=np.int64)
+    ref = oracle.expert_ffn_sliced(host_bf16_bits(x_s[: int(off[-1])]), off, cfg.E_loc, W, rows=rows)
+    check_ffn_error(ffn_error(host_bf16_bits(y_s[: int(off[-1])]), ref, off, rows=rows), cfg.weight_dtype, "graph replay")
+
+
 def run_path(lib, cfg, r, which="greedy", x_seed=0, x_on_device=False):
     """histogram -> decomposition -> slice table -> FFN on the GPU; returns everything on the host (x and y stay on
     the device when x_on_device: the checker reads back the rows it compares)."""
